@@ -1,0 +1,81 @@
+"""Checks that the oracle's pins have teeth: plant one plausible mistake at a time in a COPY of the oracle's
+C source (on the CPU, in a temp dir), point the pin tests at that build, and require that at least one pin
+fails.  The real oracle is never modified."""
+import os
+
+import pytest
+
+from oracle import lckv_oracle as orc
+import test_oracle_pins as pins
+
+SRC = os.path.join(os.path.dirname(orc.__file__), "lckv_oracle.c")
+
+MUTANTS = {
+    "scale dropped": ("s[j] = scale * dot;", "s[j] = dot;"),
+    "exponent sign flipped": ("exp(s[j] - smax)", "exp(smax - s[j])"),
+    "max not subtracted": ("exp(s[j] - smax)", "exp(s[j])"),
+    "scores taken against V": ("const float *k = K + j * row_stride;", "const float *k = V + j * row_stride;"),
+    "values taken from K": ("const float *v = V + j * row_stride;", "const float *v = K + j * row_stride;"),
+    "not normalised": ("double p = s[j] / denom;", "double p = s[j];"),
+    "self always visible": ("(self_visible[l] ? 1 : 0)", "1"),
+    "self never visible": ("(self_visible[l] ? 1 : 0)", "0"),
+    "gqa heads interleaved": ("g = h / G;", "g = h % Hkv;"),
+    "append one position early": ("b * seq + (int64_t)lens[b] * row;",
+                                  "b * seq + (int64_t)(lens[b] > 0 ? lens[b] - 1 : 0) * row;"),
+    "append V from k_new": ("memcpy(Vc + dst, v_new + src", "memcpy(Vc + dst, k_new + src"),
+    "rule 1 uses last layer": (": top_condensed;", ": L - 1;"),
+    "rule 2 uses top condensed": ("(rule == LCKV_ORACLE_PAIR_LAST_LAYER) ? L - 1", "(rule == 7) ? L - 1"),
+    "every layer reads slot 0": ("const int s = kv_slot[l];", "const int s = 0;"),
+    "lengths not bumped": ("lens[b] += 1;", "lens[b] += 0;"),
+    "warmup reads shared slot": ("kv_slot[l] = slot_of_layer[l];",
+                                 "kv_slot[l] = slot_of_layer[shared_producer < 0 ? l : shared_producer];"),
+    "kv head stride wrong": ("b * seq + (int64_t)g * D;", "b * seq + (int64_t)g;"),
+}
+
+PIN_FUNCS = [getattr(pins, n) for n in dir(pins) if n.startswith("test_")]
+
+
+def _run_all_pins():
+    """Run every pin (expanding its parametrisation by hand); return the names of those that fail."""
+    failed = []
+    for f in PIN_FUNCS:
+        marks = [m for m in getattr(f, "pytestmark", []) if m.name == "parametrize"]
+        cases = [{}]
+        for m in marks:
+            names = [s.strip() for s in m.args[0].split(",")]
+            new = []
+            for c in cases:
+                for vals in m.args[1]:
+                    vals = vals if len(names) > 1 else (vals,)
+                    new.append({**c, **dict(zip(names, vals))})
+            cases = new
+        for kw in cases:
+            try:
+                f(**kw)
+            except BaseException as e:  # noqa: BLE001 - any failure of a pin counts as "caught"
+                if isinstance(e, KeyboardInterrupt):
+                    raise
+                failed.append(f.__name__)
+                break
+    return failed
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_planted_mistake_is_caught(name, tmp_path):
+    old, new = MUTANTS[name]
+    src = open(SRC).read()
+    assert src.count(old) == 1, "mutation site %r must occur exactly once in the oracle" % old
+    mutant_c = tmp_path / "mutant.c"
+    mutant_c.write_text(src.replace(old, new))
+    lib = orc.compile_c(str(mutant_c), str(tmp_path / "libmutant.so"))
+    try:
+        orc.use_library(lib)
+        failed = _run_all_pins()
+    finally:
+        orc.use_library(None)
+    assert failed, "no pin noticed the planted mistake: " + name
+
+
+def test_unmutated_oracle_passes_the_same_runner():
+    orc.use_library(None)
+    assert _run_all_pins() == []
