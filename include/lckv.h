@@ -1,0 +1,165 @@
+/*
+ * lckv.h - C ABI of the MI355X (gfx950) decode-attention library for the Layer-Condensed KV Cache model
+ * (Wu & Tu, "Layer-Condensed KV Cache for Efficient Inference of Large Language Models").
+ *
+ * One decode step of that model (Section 2.1, Figure 1b): the queries of every non-warmup ("condensed")
+ * layer attend to ONE shared KV cache that holds only the top layer's keys and values, with the diagonal
+ * masked (the token being decoded is not visible to itself); the few warmup layers keep standard attention
+ * over caches of their own (themselves included); the step stores the new token's K/V of every producing
+ * layer.  A "slot" is one layer's worth of K and V cache.
+ *
+ * Conventions
+ *   - Every function returns LCKV_OK (0) or a negative LCKV_ERR_* code; nothing throws, nothing aborts.
+ *   - "device" pointers are HIP device memory on the current device, "host" pointers are ordinary memory.
+ *   - The caller owns every buffer and the stream.  The library owns only the handle and a few small device
+ *     tables.  Unless stated, a call only enqueues work on `hip_stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and does not synchronise; it performs no allocation after
+ *     lckv_cache_alloc, so it may be captured into a HIP graph.
+ *   - Tensors are dense, row-major, in the cache's element type (bf16 or fp32), 16-byte aligned.
+ *   - Sequence lengths live on the device (int32[B]): t_b = tokens already cached for sequence b.
+ *
+ * Physical cache layout (private to the library, stated so that storage can be sized and reasoned about):
+ * a slot is an array of "page pairs"; a page pair holds 16 consecutive positions of one kv head, first the K
+ * page then the V page, each 16*D*elem bytes, stored in the register order of the matrix instructions that
+ * consume them (bf16) or row-major [16][D] (fp32).  Contiguous caches index page pairs as
+ * [b][kv_head][page]; paged caches as [physical_block][kv_head] with physical_block = table[b][page].
+ * Only lckv_append_kv / lckv_cache_load_dense write it and lckv_cache_read reads it back logically.
+ */
+#ifndef LCKV_H
+#define LCKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LCKV_OK 0
+#define LCKV_ERR_NULL (-1)          /* a required pointer is NULL */
+#define LCKV_ERR_CONFIG (-2)        /* unsupported or inconsistent lckv_config field */
+#define LCKV_ERR_LAYER (-3)         /* layer or slot index out of range */
+#define LCKV_ERR_NOT_PRODUCER (-4)  /* lckv_append_kv on a layer whose K/V no slot stores */
+#define LCKV_ERR_BATCH (-5)         /* B < 1 or B > B_max */
+#define LCKV_ERR_LENGTH (-6)        /* max_len_hint (+1 new token) exceeds the cache capacity */
+#define LCKV_ERR_WORKSPACE (-7)     /* workspace NULL, misaligned or smaller than lckv_workspace_bytes */
+#define LCKV_ERR_ALIGN (-8)         /* a device pointer is not aligned as required */
+#define LCKV_ERR_BLOCK_TABLE (-9)   /* paged cache used before lckv_cache_set_block_table, or bad table */
+#define LCKV_ERR_HIP (-10)          /* a HIP runtime call failed (launch, copy, event) */
+#define LCKV_ERR_MASK (-11)         /* warmup_mask passed to a call differs from the cache's */
+#define LCKV_ERR_STORAGE (-12)      /* kv_storage smaller than lckv_cache_bytes */
+#define LCKV_ERR_RANGE (-13)        /* position / count out of range in a cache accessor */
+
+#define LCKV_BF16 0
+#define LCKV_F32 1
+
+/* Which layer produces the shared slot (the paper says "the top layer", Section 2.1, and leaves open what
+ * that means when the topmost layers are warmup layers):
+ *   TOP_OF_CONDENSED (default): the topmost non-warmup layer; every warmup layer has a slot of its own,
+ *                               so there are w + 1 slots for 0 < w < L.
+ *   LAST_LAYER: layer L-1 even when it is a warmup layer (it then reads that slot with itself visible). */
+#define LCKV_PAIR_TOP_OF_CONDENSED 0
+#define LCKV_PAIR_LAST_LAYER 1
+
+/* Sticky device-side error bits reported by lckv_last_device_error. */
+#define LCKV_DEV_ERR_CAPACITY 1     /* a sequence length reached the capacity; the access was skipped/clamped */
+#define LCKV_DEV_ERR_BLOCK 2        /* a block-table entry was outside [0, num_blocks); the page was skipped */
+
+typedef struct lckv_cache lckv_cache; /* opaque */
+
+typedef struct lckv_config {
+    int32_t L;            /* layers, 1..1024 */
+    int32_t Hq;           /* query heads */
+    int32_t Hkv;          /* kv heads; Hq % Hkv == 0 and Hq / Hkv <= 16; query head h reads kv head h / (Hq/Hkv) */
+    int32_t D;            /* head dimension: 64 or 128 */
+    int32_t dtype;        /* LCKV_BF16 (bf16 storage, fp32 accumulation) or LCKV_F32 */
+    int32_t B_max;        /* sequences the cache can hold (contiguous layout); upper bound on B in every call */
+    int32_t T_max;        /* contiguous layout: positions per sequence (rounded up to a multiple of 16) */
+    int32_t page_size;    /* 0 = contiguous, 16 = paged with a block table */
+    int64_t num_blocks;   /* paged only: physical 16-token blocks per slot */
+    const uint8_t *warmup_mask; /* host, L bytes, 1 = warmup layer (Section 2.1); copied */
+    int32_t pairing_rule; /* LCKV_PAIR_* */
+    float scale;          /* softmax scale; 0 means 1/sqrt(D) (the paper does not state it) */
+} lckv_config;
+
+/* Bytes of device storage a cache with this config needs (all slots).  Host only. */
+int lckv_cache_bytes(const lckv_config *cfg, size_t *bytes);
+
+/* Build the pairing table of Section 2.1 from cfg->warmup_mask and bind the caller's device storage
+ * (kv_storage, 256-byte aligned, at least lckv_cache_bytes; NOT cleared, NOT freed by the library).
+ * Allocates the handle and small device tables.  All config errors are found before any GPU call. */
+int lckv_cache_alloc(const lckv_config *cfg, void *kv_storage, size_t kv_bytes, lckv_cache **out);
+int lckv_cache_free(lckv_cache *cache);
+
+/* Paged caches: device table int32[B_max][max_blocks_per_seq]; entry [b][p] is the physical block holding
+ * positions 16p..16p+15 of sequence b in EVERY slot (one table serves all slots).  Borrowed, not copied: it
+ * must stay valid, and may be updated by the caller between calls.  Capacity per sequence becomes
+ * 16 * max_blocks_per_seq. */
+int lckv_cache_set_block_table(lckv_cache *cache, const int32_t *dev_table, int32_t max_blocks_per_seq);
+
+/* Pairing table (Section 2.1): number of slots; the slot layer `layer` reads and whether the token being
+ * decoded is visible to it (1 for warmup layers, 0 for condensed layers: diagonal mask); the layer whose new
+ * K/V go to `slot`.  Slots are numbered by ascending producer layer.  Host only. */
+int lckv_n_slots(const lckv_cache *cache, int32_t *n_slots);
+int lckv_kv_slot(const lckv_cache *cache, int32_t layer, int32_t *slot, int32_t *self_visible);
+int lckv_slot_producer(const lckv_cache *cache, int32_t slot, int32_t *layer);
+
+/* Store the new token's K/V of a producing layer: for every b < B,
+ *   K[slot(layer)][b][t_b] = k_new[b], V[...] = v_new[b]      (bits copied unchanged)
+ * k_new, v_new: device [B][Hkv][D].  dev_seq_lens: device int32[B], read, not changed.
+ * A sequence already at capacity is skipped and LCKV_DEV_ERR_CAPACITY is raised on the device. */
+int lckv_append_kv(lckv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
+                   const int32_t *dev_seq_lens, int32_t B, void *hip_stream);
+
+/* Attention of one layer's queries for one decode step (Section 2.1):
+ *   out[b][h] = softmax_j(scale * <q[b][h], K[slot][b][j][h/G]>) . V[slot][b][j][h/G],   j < n_b,
+ * n_b = t_b for a condensed layer (diagonal masked), t_b + 1 for a warmup layer (the caller has appended
+ * this layer's new K/V first).  n_b = 0 gives the zero vector (the paper's zero dummy K/V for the first
+ * token).  q, out: device [B][Hq][D].  warmup_mask: optional host array of L bytes; if not NULL it must
+ * equal the cache's mask (LCKV_ERR_MASK otherwise).  max_len_hint: host-side upper bound on every t_b
+ * (lengths above it are clamped and raise LCKV_DEV_ERR_CAPACITY); it fixes the split of the key range.
+ * workspace: device scratch for split partials, 256-byte aligned, at least lckv_workspace_bytes. */
+int lckv_decode_attention(lckv_cache *cache, int32_t layer, const void *q, void *out,
+                          const int32_t *dev_seq_lens, const uint8_t *warmup_mask, int32_t B,
+                          int32_t max_len_hint, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* The whole step: layers in index order (layer l+1 starts after layer l has finished: in the model its query
+ * depends on layer l's output); a producing layer's K/V are appended just before its attention; at the end
+ * every t_b is incremented on the device.
+ *   q_all, out_all: device [L][B][Hq][D];  k_new_all, v_new_all: device [n_slots][B][Hkv][D], slot order. */
+int lckv_step(lckv_cache *cache, const void *q_all, const void *k_new_all, const void *v_new_all, void *out_all,
+              int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint, void *workspace, size_t workspace_bytes,
+              void *hip_stream);
+
+/* Bytes of workspace lckv_decode_attention / lckv_step need for this B and max_len_hint.  Host only. */
+int lckv_workspace_bytes(const lckv_cache *cache, int32_t B, int32_t max_len_hint, size_t *bytes);
+
+/* Force the number of keys per split (a multiple of 16; 0 = choose from B, Hkv and max_len_hint).  The split
+ * of a sequence's keys never depends on other sequences' lengths.  Host only; meant for tests and tuning. */
+int lckv_set_split_tokens(lckv_cache *cache, int32_t tokens);
+
+/* Bulk import (e.g. after prompt encoding): positions [0, T) of every sequence b < B of `slot` are written from
+ * dense device tensors k, v of shape [B][T][Hkv][D].  Bits copied unchanged. */
+int lckv_cache_load_dense(lckv_cache *cache, int32_t slot, const void *k, const void *v, int32_t B, int32_t T,
+                          void *hip_stream);
+
+/* Logical read-back for tests and snapshots: positions [pos, pos + n_pos) of sequence b in `slot` are copied
+ * to host_k, host_v as [n_pos][Hkv][D].  Allocates a temporary and SYNCHRONISES the device. */
+int lckv_cache_read(lckv_cache *cache, int32_t slot, int32_t b, int32_t pos, int32_t n_pos, void *host_k,
+                    void *host_v);
+
+/* Read and clear the sticky device error bits (LCKV_DEV_ERR_*).  SYNCHRONISES the device. */
+int lckv_last_device_error(lckv_cache *cache, int32_t *bits);
+
+/* Kernel timing for benchmarks: while enabled, every attention kernel launch is bracketed by HIP events on
+ * its stream (do not enable during graph capture).  lckv_profile_read SYNCHRONISES, returns the number of
+ * timed launches and their summed duration since the last read, and resets both. */
+int lckv_profile_enable(lckv_cache *cache, int32_t enable);
+int lckv_profile_read(lckv_cache *cache, int32_t *n_launches, double *total_ms);
+
+const char *lckv_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LCKV_H */

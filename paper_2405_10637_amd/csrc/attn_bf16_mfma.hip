@@ -1,0 +1,261 @@
+// Split-KV decode attention for bf16 caches on gfx950 (Section 2.1 of the LCKV paper: one query token per
+// sequence attends to the slot its layer is paired with).
+//
+// One workgroup (4 waves) handles one (split, kv head, sequence).  All G = Hq/Hkv query heads of the kv head
+// ride in the 16 columns of the matrix tiles, so K and V are read from HBM once per kv head:
+//   S^T[key][query]  = K_page[16 keys x D]   . Q^T[D x 16 queries]      v_mfma_f32_16x16x32_bf16, D/32 steps
+//   O^T[d][query]   += V_page^T[16 d x 16 keys] . P^T[16 keys x 16 queries]   v_mfma_f32_16x16x16_bf16, D/16 tiles
+// The accumulator layout of the first product (lane (kb, c) holds keys 4kb..4kb+3 of query c) is exactly the
+// B-operand layout of the second, so probabilities never leave registers.  Pages are stored in operand order:
+// every global load is 16 bytes per lane and 1 KiB contiguous per wave.  Each wave keeps a running (max, sum,
+// O) per query (online softmax, fp32); waves are merged through LDS at the end.
+#include "lckv_internal.h"
+
+namespace lckv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float floatx2;
+typedef __attribute__((ext_vector_type(4))) float floatx4;
+typedef __attribute__((ext_vector_type(4))) short shortx4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kWaves = 4;
+constexpr float kNegInf = -__builtin_huge_valf();
+
+__device__ __forceinline__ float xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask, 64)); }
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    floatx2 f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));  // v_cvt_pk_bf16_f32, RNE
+}
+
+template <int D, int NP>
+struct Tile {
+    u32x4 k[NP][D / 32];
+    u32x4 v[NP][D / 32];
+    int page[NP];     // page number, or -1 if this part of the tile is not read
+};
+
+// Issue the loads of NP consecutive pages starting at `pg` for (b, g).
+template <int D, int NP>
+__device__ __forceinline__ void load_tile(Tile<D, NP> &t, const SlotView &sv, int b, int g, int pg, int pg_end,
+                                          int lane_off, int32_t *dev_err) {
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        int pgi = pg + i;
+        t.page[i] = -1;
+        if (pgi < pg_end) {
+            int64_t idx = page_pair_index(sv, b, g, pgi);
+            if (idx >= 0) {
+                t.page[i] = pgi;
+                const char *base = sv.base + idx * (2 * (int64_t)sv.page_bytes) + lane_off;
+#pragma unroll
+                for (int ks = 0; ks < D / 32; ++ks) t.k[i][ks] = *(const u32x4 *)(base + ks * 1024);
+#pragma unroll
+                for (int dp = 0; dp < D / 32; ++dp)
+                    t.v[i][dp] = *(const u32x4 *)(base + sv.page_bytes + dp * 1024);
+            } else if (threadIdx.x % 64 == 0) {
+                atomicOr(dev_err, LCKV_DEV_ERR_BLOCK);
+            }
+        }
+    }
+}
+
+template <int D, int NP>
+__device__ __forceinline__ void consume_tile(Tile<D, NP> &t, const bf16x8 (&qb)[D / 32], floatx4 (&acc)[D / 16],
+                                             float &m, float &l, int k_end, int kb, float c) {
+    bool any = false;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) any |= t.page[i] >= 0;
+    if (!any) return;  // every page of the tile was rejected (bad block table): nothing to add
+    floatx4 s[NP];
+    float smax = kNegInf;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        if (t.page[i] < 0) {  // wave-uniform
+            s[i] = floatx4{kNegInf, kNegInf, kNegInf, kNegInf};
+            continue;
+        }
+        floatx4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ++ks)
+            z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.k[i][ks]), qb[ks], z, 0, 0, 0);
+        int key0 = t.page[i] * kPage + 4 * kb;
+        if ((t.page[i] + 1) * kPage > k_end) {  // last, partly filled page: mask scores, clear stale values
+            int nv = k_end - key0;              // valid keys among this lane's four
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (e >= nv) z[e] = kNegInf;
+            uint32_t m01 = nv >= 2 ? 0xffffffffu : (nv == 1 ? 0x0000ffffu : 0u);
+            uint32_t m23 = nv >= 4 ? 0xffffffffu : (nv == 3 ? 0x0000ffffu : 0u);
+#pragma unroll
+            for (int dp = 0; dp < D / 32; ++dp) {
+                t.v[i][dp][0] &= m01;
+                t.v[i][dp][1] &= m23;
+                t.v[i][dp][2] &= m01;
+                t.v[i][dp][3] &= m23;
+            }
+        }
+        s[i] = z;
+        smax = fmaxf(smax, fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])));
+    }
+    // the four lanes (kb = 0..3) of a query column share one running maximum
+    smax = xor_max(smax, 16);
+    smax = xor_max(smax, 32);
+    float m_new = fmaxf(m, smax);  // finite: a page that was read always holds a visible key
+    float mb = m_new * c;
+    float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
+    m = m_new;
+    float psum = 0.f;
+    shortx4 pb[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i][0], c, -mb));
+        float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i][1], c, -mb));
+        float p2 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i][2], c, -mb));
+        float p3 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i][3], c, -mb));
+        psum += (p0 + p1) + (p2 + p3);
+        u32x2 pk = {pack_bf16(p0, p1), pack_bf16(p2, p3)};
+        pb[i] = __builtin_bit_cast(shortx4, pk);
+    }
+    l = l * alpha + psum;
+#pragma unroll
+    for (int j = 0; j < D / 16; ++j) acc[j] *= alpha;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        if (t.page[i] < 0) continue;
+#pragma unroll
+        for (int dp = 0; dp < D / 32; ++dp) {
+            u32x2 lo = {t.v[i][dp][0], t.v[i][dp][1]};
+            u32x2 hi = {t.v[i][dp][2], t.v[i][dp][3]};
+            acc[2 * dp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, lo), pb[i],
+                                                                    acc[2 * dp], 0, 0, 0);
+            acc[2 * dp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, hi), pb[i],
+                                                                        acc[2 * dp + 1], 0, 0, 0);
+        }
+    }
+}
+
+template <int D, int NP>
+__global__ __launch_bounds__(kWaves * 64) void attn_bf16_kernel(AttnParams p) {
+    const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, kb = lane >> 4;  // query column / key quad (also: page row / 16-byte column)
+    const int G = p.G;
+    const int h = g * G + c;                  // query head of this lane's column (valid if c < G)
+
+    int n = p.seq_lens[b] + p.self_visible;
+    if (n > p.max_n) {
+        n = p.max_n;
+        if (tid == 0) atomicOr(p.dev_err, LCKV_DEV_ERR_CAPACITY);
+    }
+    if (n < 0) n = 0;
+    const int k_begin = split * p.split_tokens;
+    const int k_end = min(n, k_begin + p.split_tokens);
+    const int64_t row = (int64_t)b * p.Hq + h;
+
+    if (k_begin >= k_end) {  // nothing visible in this split
+        if (p.n_splits == 1) {
+            // no visible key at all: the zero vector (zero dummy K/V of the first token, Section 2.1)
+            uint16_t *o = (uint16_t *)p.out + ((int64_t)b * p.Hq + (int64_t)g * G) * D;
+            for (int i = tid; i < G * D; i += kWaves * 64) o[i] = 0;
+        } else if (tid < G) {
+            p.part_ml[((int64_t)split * p.B + b) * p.Hq + g * G + tid] = float2{kNegInf, 0.f};
+        }
+        return;
+    }
+
+    // Q^T operands: lane (kb, c) holds channels ks*32 + 8kb .. +8 of query head h; columns >= G are zero.
+    bf16x8 qb[D / 32];
+    {
+        const char *qp = (const char *)p.q + (row * D + kb * 8) * 2;
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ++ks) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (c < G) v = *(const u32x4 *)(qp + ks * 64);
+            qb[ks] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+
+    floatx4 acc[D / 16];
+#pragma unroll
+    for (int j = 0; j < D / 16; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float m = kNegInf, l = 0.f;
+    const float cs = p.scale_log2e;
+    const int lane_off = c * 64 + kb * 16;
+    const int pg_end = (k_end + kPage - 1) / kPage;
+    constexpr int kStride = kWaves * NP;
+
+    // two tiles in flight per wave: the loads of the next tile are issued before the current one is used
+    int pg = k_begin / kPage + wave * NP;
+    Tile<D, NP> ta, tb;
+    if (pg < pg_end) load_tile<D, NP>(ta, p.slot, b, g, pg, pg_end, lane_off, p.dev_err);
+    while (pg < pg_end) {
+        if (pg + kStride < pg_end) load_tile<D, NP>(tb, p.slot, b, g, pg + kStride, pg_end, lane_off, p.dev_err);
+        consume_tile<D, NP>(ta, qb, acc, m, l, k_end, kb, cs);
+        pg += kStride;
+        if (pg >= pg_end) break;
+        if (pg + kStride < pg_end) load_tile<D, NP>(ta, p.slot, b, g, pg + kStride, pg_end, lane_off, p.dev_err);
+        consume_tile<D, NP>(tb, qb, acc, m, l, k_end, kb, cs);
+        pg += kStride;
+    }
+
+    // denominators were kept per lane: add the four key quads of each column
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+
+    // merge the four waves: (m, l, O) per query column through LDS
+    __shared__ float sm_m[kWaves][16];
+    __shared__ float sm_l[kWaves][16];
+    __shared__ floatx4 sm_acc[kWaves][D / 16][64];
+    if (kb == 0) {
+        sm_m[wave][c] = m * cs;  // log2 units; -inf for a wave that saw no page
+        sm_l[wave][c] = l;
+    }
+#pragma unroll
+    for (int j = 0; j < D / 16; ++j) sm_acc[wave][j][lane] = acc[j];
+    __syncthreads();
+
+    float M = kNegInf;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sm_m[w][c]);
+    float f[kWaves], L = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        float mw = sm_m[w][c];
+        f[w] = (mw == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+        L += f[w] * sm_l[w][c];
+    }
+    // wave w finishes channel tiles w, w + 4, ...
+    for (int j = wave; j < D / 16; j += kWaves) {
+        floatx4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w)
+            if (f[w] != 0.f) o += f[w] * sm_acc[w][j][lane];
+        if (c < G) {
+            int d0 = j * 16 + 4 * kb;  // this lane holds channels d0..d0+3 of query head h
+            if (p.n_splits == 1) {
+                float inv = L > 0.f ? 1.f / L : 0.f;
+                u32x2 pk = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv)};
+                *(u32x2 *)((uint16_t *)p.out + row * D + d0) = pk;
+            } else {
+                *(floatx4 *)(p.part_o + (((int64_t)split * p.B + b) * p.Hq + h) * D + d0) = o;
+            }
+        }
+    }
+    if (p.n_splits > 1 && wave == 0 && kb == 0 && c < G)
+        p.part_ml[((int64_t)split * p.B + b) * p.Hq + h] = float2{M, L};
+}
+
+hipError_t launch_attn_bf16(const AttnParams &p, int D, hipStream_t s) {
+    dim3 grid(p.n_splits, p.Hkv, p.B), block(kWaves * 64);
+    if (D == 128)
+        hipLaunchKernelGGL((attn_bf16_kernel<128, 2>), grid, block, 0, s, p);
+    else
+        hipLaunchKernelGGL((attn_bf16_kernel<64, 2>), grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace lckv

@@ -1,0 +1,446 @@
+// Host side of liblckv: argument checks, the pairing table of Section 2.1, split planning and kernel launches.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+
+#include "lckv_internal.h"
+
+using namespace lckv;
+
+namespace {
+
+constexpr uint64_t kMagic = 0x4c434b5643414348ull;  // "LCKVCACH"
+constexpr size_t kProfilePairs = 4096;
+constexpr int kTargetWorkgroups = 2048;  // 8 per compute unit: enough to hide the tail of the last wave of groups
+constexpr int kMinSplitTokens = 256;
+
+bool valid(const lckv_cache *c) { return c && c->magic == kMagic; }
+
+int elem_bytes(int dtype) { return dtype == LCKV_BF16 ? 2 : 4; }
+
+int check_config(const lckv_config *cfg) {
+    if (!cfg) return LCKV_ERR_NULL;
+    if (!cfg->warmup_mask) return LCKV_ERR_NULL;
+    if (cfg->L < 1 || cfg->L > 1024) return LCKV_ERR_CONFIG;
+    if (cfg->Hq < 1 || cfg->Hkv < 1 || cfg->Hq % cfg->Hkv != 0) return LCKV_ERR_CONFIG;
+    if (cfg->Hq / cfg->Hkv > kMaxGroup) return LCKV_ERR_CONFIG;
+    if (cfg->Hq > 65535) return LCKV_ERR_CONFIG;
+    if (cfg->D != 64 && cfg->D != 128) return LCKV_ERR_CONFIG;
+    if (cfg->dtype != LCKV_BF16 && cfg->dtype != LCKV_F32) return LCKV_ERR_CONFIG;
+    if (cfg->B_max < 1 || cfg->B_max > 65535) return LCKV_ERR_CONFIG;
+    if (cfg->page_size != 0 && cfg->page_size != kPage) return LCKV_ERR_CONFIG;
+    if (cfg->page_size == 0 && (cfg->T_max < 1 || cfg->T_max > (1 << 24))) return LCKV_ERR_CONFIG;
+    if (cfg->page_size == kPage && (cfg->num_blocks < 1 || cfg->num_blocks > (int64_t)1 << 31)) return LCKV_ERR_CONFIG;
+    if (cfg->pairing_rule != LCKV_PAIR_TOP_OF_CONDENSED && cfg->pairing_rule != LCKV_PAIR_LAST_LAYER)
+        return LCKV_ERR_CONFIG;
+    if (!(cfg->scale >= 0.f) || isinf(cfg->scale)) return LCKV_ERR_CONFIG;
+    for (int l = 0; l < cfg->L; ++l)
+        if (cfg->warmup_mask[l] > 1) return LCKV_ERR_CONFIG;
+    return LCKV_OK;
+}
+
+// Section 2.1: warmup layers keep standard attention on caches of their own; all other layers read the one
+// cache of "the top layer" with the diagonal masked.  Slots are numbered by ascending producer layer.
+void build_pairing(const lckv_config &cfg, std::vector<int32_t> &kv_slot, std::vector<int32_t> &self_visible,
+                   std::vector<int32_t> &producer) {
+    const int L = cfg.L;
+    const uint8_t *warm = cfg.warmup_mask;
+    int shared_from = -1;
+    for (int l = L - 1; l >= 0; --l)
+        if (!warm[l]) {
+            shared_from = cfg.pairing_rule == LCKV_PAIR_LAST_LAYER ? L - 1 : l;
+            break;
+        }
+    std::vector<int32_t> slot_of(L, -1);
+    producer.clear();
+    for (int l = 0; l < L; ++l)
+        if (warm[l] || l == shared_from) {
+            slot_of[l] = (int32_t)producer.size();
+            producer.push_back(l);
+        }
+    kv_slot.assign(L, 0);
+    self_visible.assign(L, 0);
+    for (int l = 0; l < L; ++l) {
+        kv_slot[l] = warm[l] ? slot_of[l] : slot_of[shared_from];
+        self_visible[l] = warm[l] ? 1 : 0;
+    }
+}
+
+struct Geometry {
+    int32_t n_slots, pages_per_seq, page_bytes;
+    size_t slot_bytes;
+};
+
+Geometry geometry(const lckv_config &cfg) {
+    std::vector<int32_t> a, b, prod;
+    build_pairing(cfg, a, b, prod);
+    Geometry g;
+    g.n_slots = (int32_t)prod.size();
+    g.page_bytes = kPage * cfg.D * elem_bytes(cfg.dtype);
+    g.pages_per_seq = cfg.page_size ? 0 : (cfg.T_max + kPage - 1) / kPage;
+    size_t pairs = cfg.page_size ? (size_t)cfg.num_blocks * cfg.Hkv
+                                 : (size_t)cfg.B_max * cfg.Hkv * (size_t)g.pages_per_seq;
+    g.slot_bytes = pairs * 2 * (size_t)g.page_bytes;
+    return g;
+}
+
+SlotView slot_view(const lckv_cache *c, int slot) {
+    SlotView v;
+    v.base = c->storage + (size_t)slot * c->slot_bytes;
+    v.table = c->table;
+    v.max_blocks = c->max_blocks;
+    v.num_blocks = c->cfg.num_blocks;
+    v.pages_per_seq = c->pages_per_seq;
+    v.Hkv = c->cfg.Hkv;
+    v.page_bytes = c->page_bytes;
+    v.capacity = c->capacity;
+    return v;
+}
+
+struct SplitPlan {
+    int32_t tokens, n_splits;
+};
+
+// Keys per split: fixed by B, Hkv and the length bound only, never by an individual sequence's length, so a
+// sequence's result does not depend on which other sequences share the batch.
+SplitPlan plan_splits(const lckv_cache *c, int B, int max_n) {
+    SplitPlan p;
+    if (max_n < 1) max_n = 1;
+    if (c->forced_split_tokens > 0) {
+        p.tokens = c->forced_split_tokens;
+    } else {
+        int64_t units = (int64_t)B * c->cfg.Hkv;
+        int64_t want = (kTargetWorkgroups + units - 1) / units;
+        int64_t most = max_n / kMinSplitTokens;
+        if (most < 1) most = 1;
+        if (want > most) want = most;
+        if (want < 1) want = 1;
+        int64_t t = (max_n + want - 1) / want;
+        p.tokens = (int32_t)((t + 63) / 64 * 64);
+    }
+    p.n_splits = (max_n + p.tokens - 1) / p.tokens;
+    return p;
+}
+
+size_t workspace_need(const lckv_cache *c, int B, int n_splits) {
+    if (n_splits <= 1) return 0;
+    size_t rows = (size_t)n_splits * B * c->cfg.Hq;
+    size_t o = rows * c->cfg.D * sizeof(float);
+    size_t ml = rows * sizeof(float2);
+    return (o + 255) / 256 * 256 + (ml + 255) / 256 * 256;
+}
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+int attention_impl(lckv_cache *c, int layer, const void *q, void *out, const int32_t *lens, int B, int max_len_hint,
+                   void *workspace, size_t workspace_bytes, hipStream_t stream) {
+    const lckv_config &cfg = c->cfg;
+    const int self = c->self_visible[layer];
+    const int max_n = max_len_hint + self;
+    SplitPlan sp = plan_splits(c, B, max_n);
+    size_t need = workspace_need(c, B, sp.n_splits);
+    if (need > 0) {
+        if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return LCKV_ERR_WORKSPACE;
+    }
+    AttnParams p;
+    p.slot = slot_view(c, c->kv_slot[layer]);
+    p.q = q;
+    p.out = out;
+    p.seq_lens = lens;
+    size_t rows = (size_t)sp.n_splits * B * cfg.Hq;
+    p.part_o = (float *)workspace;
+    p.part_ml = need ? (float2 *)((char *)workspace + (rows * cfg.D * sizeof(float) + 255) / 256 * 256) : nullptr;
+    p.dev_err = c->dev_err;
+    p.B = B;
+    p.Hq = cfg.Hq;
+    p.Hkv = cfg.Hkv;
+    p.G = cfg.Hq / cfg.Hkv;
+    p.self_visible = self;
+    p.max_n = max_n;
+    p.split_tokens = sp.tokens;
+    p.n_splits = sp.n_splits;
+    p.scale_log2e = c->scale * 1.4426950408889634f;
+
+    const bool timed = c->profiling && c->ev_used + 2 <= c->ev.size();
+    if (timed && hipEventRecord(c->ev[c->ev_used], stream) != hipSuccess) return LCKV_ERR_HIP;
+    hipError_t e = cfg.dtype == LCKV_BF16 ? launch_attn_bf16(p, cfg.D, stream) : launch_attn_f32(p, cfg.D, stream);
+    if (e != hipSuccess) return LCKV_ERR_HIP;
+    if (timed) {
+        if (hipEventRecord(c->ev[c->ev_used + 1], stream) != hipSuccess) return LCKV_ERR_HIP;
+        c->ev_used += 2;
+    }
+    if (sp.n_splits > 1 && launch_combine(p, cfg.D, cfg.dtype, stream) != hipSuccess) return LCKV_ERR_HIP;
+    return LCKV_OK;
+}
+
+int check_call(const lckv_cache *c, int B, int max_len_hint, int extra) {
+    if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
+    if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
+    if (max_len_hint < 0 || (int64_t)max_len_hint + extra > c->capacity) return LCKV_ERR_LENGTH;
+    return LCKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lckv_cache_bytes(const lckv_config *cfg, size_t *bytes) {
+    if (!bytes) return LCKV_ERR_NULL;
+    int rc = check_config(cfg);
+    if (rc != LCKV_OK) return rc;
+    Geometry g = geometry(*cfg);
+    *bytes = g.slot_bytes * (size_t)g.n_slots;
+    return LCKV_OK;
+}
+
+int lckv_cache_alloc(const lckv_config *cfg, void *kv_storage, size_t kv_bytes, lckv_cache **out) {
+    if (!out) return LCKV_ERR_NULL;
+    *out = nullptr;
+    int rc = check_config(cfg);
+    if (rc != LCKV_OK) return rc;
+    if (!kv_storage) return LCKV_ERR_NULL;
+    if (!aligned(kv_storage, 256)) return LCKV_ERR_ALIGN;
+    Geometry g = geometry(*cfg);
+    if (kv_bytes < g.slot_bytes * (size_t)g.n_slots) return LCKV_ERR_STORAGE;
+
+    lckv_cache *c = new (std::nothrow) lckv_cache();
+    if (!c) return LCKV_ERR_HIP;
+    c->magic = kMagic;
+    c->cfg = *cfg;
+    c->warm.assign(cfg->warmup_mask, cfg->warmup_mask + cfg->L);
+    c->cfg.warmup_mask = c->warm.data();
+    build_pairing(c->cfg, c->kv_slot, c->self_visible, c->producer);
+    c->n_slots = g.n_slots;
+    c->storage = (char *)kv_storage;
+    c->slot_bytes = g.slot_bytes;
+    c->pages_per_seq = g.pages_per_seq;
+    c->page_bytes = g.page_bytes;
+    c->table = nullptr;
+    c->max_blocks = 0;
+    c->capacity = cfg->page_size ? 0 : g.pages_per_seq * kPage;
+    c->forced_split_tokens = 0;
+    c->scale = cfg->scale > 0.f ? cfg->scale : 1.0f / sqrtf((float)cfg->D);
+    c->profiling = false;
+    c->ev_used = 0;
+    c->dev_err = nullptr;
+    if (hipMalloc((void **)&c->dev_err, 256) != hipSuccess || hipMemset(c->dev_err, 0, 256) != hipSuccess) {
+        if (c->dev_err) (void)hipFree(c->dev_err);
+        c->magic = 0;
+        delete c;
+        return LCKV_ERR_HIP;
+    }
+    *out = c;
+    return LCKV_OK;
+}
+
+int lckv_cache_free(lckv_cache *c) {
+    if (!valid(c)) return LCKV_ERR_NULL;
+    for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+    if (c->dev_err) (void)hipFree(c->dev_err);
+    c->magic = 0;
+    delete c;
+    return LCKV_OK;
+}
+
+int lckv_cache_set_block_table(lckv_cache *c, const int32_t *dev_table, int32_t max_blocks_per_seq) {
+    if (!valid(c) || !dev_table) return LCKV_ERR_NULL;
+    if (!c->cfg.page_size) return LCKV_ERR_BLOCK_TABLE;
+    if (max_blocks_per_seq < 1 || max_blocks_per_seq > (1 << 24) / kPage) return LCKV_ERR_BLOCK_TABLE;
+    if (!aligned(dev_table, 4)) return LCKV_ERR_ALIGN;
+    c->table = dev_table;
+    c->max_blocks = max_blocks_per_seq;
+    c->capacity = max_blocks_per_seq * kPage;
+    return LCKV_OK;
+}
+
+int lckv_n_slots(const lckv_cache *c, int32_t *n_slots) {
+    if (!valid(c) || !n_slots) return LCKV_ERR_NULL;
+    *n_slots = c->n_slots;
+    return LCKV_OK;
+}
+
+int lckv_kv_slot(const lckv_cache *c, int32_t layer, int32_t *slot, int32_t *self_visible) {
+    if (!valid(c) || !slot || !self_visible) return LCKV_ERR_NULL;
+    if (layer < 0 || layer >= c->cfg.L) return LCKV_ERR_LAYER;
+    *slot = c->kv_slot[layer];
+    *self_visible = c->self_visible[layer];
+    return LCKV_OK;
+}
+
+int lckv_slot_producer(const lckv_cache *c, int32_t slot, int32_t *layer) {
+    if (!valid(c) || !layer) return LCKV_ERR_NULL;
+    if (slot < 0 || slot >= c->n_slots) return LCKV_ERR_LAYER;
+    *layer = c->producer[slot];
+    return LCKV_OK;
+}
+
+int lckv_append_kv(lckv_cache *c, int32_t layer, const void *k_new, const void *v_new, const int32_t *dev_seq_lens,
+                   int32_t B, void *hip_stream) {
+    if (!valid(c) || !k_new || !v_new || !dev_seq_lens) return LCKV_ERR_NULL;
+    if (layer < 0 || layer >= c->cfg.L) return LCKV_ERR_LAYER;
+    int slot = -1;
+    for (int s = 0; s < c->n_slots; ++s)
+        if (c->producer[s] == layer) slot = s;
+    if (slot < 0) return LCKV_ERR_NOT_PRODUCER;
+    if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
+    if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
+    if (!aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(dev_seq_lens, 4)) return LCKV_ERR_ALIGN;
+    hipError_t e = launch_append(slot_view(c, slot), k_new, v_new, dev_seq_lens, B, c->cfg.D, c->cfg.dtype,
+                                 c->dev_err, (hipStream_t)hip_stream);
+    return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
+}
+
+int lckv_decode_attention(lckv_cache *c, int32_t layer, const void *q, void *out, const int32_t *dev_seq_lens,
+                          const uint8_t *warmup_mask, int32_t B, int32_t max_len_hint, void *workspace,
+                          size_t workspace_bytes, void *hip_stream) {
+    if (!valid(c) || !q || !out || !dev_seq_lens) return LCKV_ERR_NULL;
+    if (layer < 0 || layer >= c->cfg.L) return LCKV_ERR_LAYER;
+    if (warmup_mask && memcmp(warmup_mask, c->warm.data(), (size_t)c->cfg.L) != 0) return LCKV_ERR_MASK;
+    int rc = check_call(c, B, max_len_hint, c->self_visible[layer]);
+    if (rc != LCKV_OK) return rc;
+    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(dev_seq_lens, 4)) return LCKV_ERR_ALIGN;
+    return attention_impl(c, layer, q, out, dev_seq_lens, B, max_len_hint, workspace, workspace_bytes,
+                          (hipStream_t)hip_stream);
+}
+
+int lckv_step(lckv_cache *c, const void *q_all, const void *k_new_all, const void *v_new_all, void *out_all,
+              int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint, void *workspace, size_t workspace_bytes,
+              void *hip_stream) {
+    if (!valid(c) || !q_all || !k_new_all || !v_new_all || !out_all || !dev_seq_lens) return LCKV_ERR_NULL;
+    int rc = check_call(c, B, max_len_hint, 1);  // the new token must fit
+    if (rc != LCKV_OK) return rc;
+    if (!aligned(q_all, 16) || !aligned(out_all, 16) || !aligned(k_new_all, 16) || !aligned(v_new_all, 16) ||
+        !aligned(dev_seq_lens, 4))
+        return LCKV_ERR_ALIGN;
+    size_t need = 0;
+    rc = lckv_workspace_bytes(c, B, max_len_hint, &need);
+    if (rc != LCKV_OK) return rc;
+    if (need > 0 && (!workspace || !aligned(workspace, 256) || workspace_bytes < need)) return LCKV_ERR_WORKSPACE;
+
+    const lckv_config &cfg = c->cfg;
+    const size_t eb = (size_t)elem_bytes(cfg.dtype);
+    const size_t q_layer = (size_t)B * cfg.Hq * cfg.D * eb;
+    const size_t kv_slot_sz = (size_t)B * cfg.Hkv * cfg.D * eb;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    for (int l = 0; l < cfg.L; ++l) {
+        for (int s = 0; s < c->n_slots; ++s) {
+            if (c->producer[s] != l) continue;
+            hipError_t e = launch_append(slot_view(c, s), (const char *)k_new_all + s * kv_slot_sz,
+                                         (const char *)v_new_all + s * kv_slot_sz, dev_seq_lens, B, cfg.D, cfg.dtype,
+                                         c->dev_err, stream);
+            if (e != hipSuccess) return LCKV_ERR_HIP;
+        }
+        rc = attention_impl(c, l, (const char *)q_all + l * q_layer, (char *)out_all + l * q_layer, dev_seq_lens, B,
+                            max_len_hint, workspace, workspace_bytes, stream);
+        if (rc != LCKV_OK) return rc;
+    }
+    return launch_bump(dev_seq_lens, B, stream) == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
+}
+
+int lckv_workspace_bytes(const lckv_cache *c, int32_t B, int32_t max_len_hint, size_t *bytes) {
+    if (!valid(c) || !bytes) return LCKV_ERR_NULL;
+    if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
+    if (max_len_hint < 0) return LCKV_ERR_LENGTH;
+    size_t a = workspace_need(c, B, plan_splits(c, B, max_len_hint).n_splits);
+    size_t b = workspace_need(c, B, plan_splits(c, B, max_len_hint + 1).n_splits);
+    *bytes = a > b ? a : b;
+    return LCKV_OK;
+}
+
+int lckv_set_split_tokens(lckv_cache *c, int32_t tokens) {
+    if (!valid(c)) return LCKV_ERR_NULL;
+    if (tokens < 0 || tokens % kPage != 0) return LCKV_ERR_CONFIG;
+    c->forced_split_tokens = tokens;
+    return LCKV_OK;
+}
+
+int lckv_cache_load_dense(lckv_cache *c, int32_t slot, const void *k, const void *v, int32_t B, int32_t T,
+                          void *hip_stream) {
+    if (!valid(c) || !k || !v) return LCKV_ERR_NULL;
+    if (slot < 0 || slot >= c->n_slots) return LCKV_ERR_LAYER;
+    if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
+    if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
+    if (T < 0 || T > c->capacity) return LCKV_ERR_LENGTH;
+    hipError_t e = launch_load_dense(slot_view(c, slot), k, v, B, T, c->cfg.D, c->cfg.dtype, c->dev_err,
+                                     (hipStream_t)hip_stream);
+    return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
+}
+
+int lckv_cache_read(lckv_cache *c, int32_t slot, int32_t b, int32_t pos, int32_t n_pos, void *host_k, void *host_v) {
+    if (!valid(c) || !host_k || !host_v) return LCKV_ERR_NULL;
+    if (slot < 0 || slot >= c->n_slots) return LCKV_ERR_LAYER;
+    if (b < 0 || b >= c->cfg.B_max) return LCKV_ERR_BATCH;
+    if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
+    if (pos < 0 || n_pos < 1 || (int64_t)pos + n_pos > c->capacity) return LCKV_ERR_RANGE;
+    size_t bytes = (size_t)n_pos * c->cfg.Hkv * c->cfg.D * elem_bytes(c->cfg.dtype);
+    char *tmp = nullptr;
+    if (hipMalloc((void **)&tmp, 2 * bytes) != hipSuccess) return LCKV_ERR_HIP;
+    int rc = LCKV_OK;
+    if (launch_gather(slot_view(c, slot), b, pos, n_pos, c->cfg.D, c->cfg.dtype, tmp, tmp + bytes, c->dev_err,
+                      nullptr) != hipSuccess ||
+        hipDeviceSynchronize() != hipSuccess || hipMemcpy(host_k, tmp, bytes, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(host_v, tmp + bytes, bytes, hipMemcpyDeviceToHost) != hipSuccess)
+        rc = LCKV_ERR_HIP;
+    (void)hipFree(tmp);
+    return rc;
+}
+
+int lckv_last_device_error(lckv_cache *c, int32_t *bits) {
+    if (!valid(c) || !bits) return LCKV_ERR_NULL;
+    if (hipDeviceSynchronize() != hipSuccess) return LCKV_ERR_HIP;
+    if (hipMemcpy(bits, c->dev_err, sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess) return LCKV_ERR_HIP;
+    if (*bits && hipMemset(c->dev_err, 0, sizeof(int32_t)) != hipSuccess) return LCKV_ERR_HIP;
+    return LCKV_OK;
+}
+
+int lckv_profile_enable(lckv_cache *c, int32_t enable) {
+    if (!valid(c)) return LCKV_ERR_NULL;
+    if (enable && c->ev.empty()) {
+        c->ev.reserve(2 * kProfilePairs);
+        for (size_t i = 0; i < 2 * kProfilePairs; ++i) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return LCKV_ERR_HIP;
+            c->ev.push_back(e);
+        }
+    }
+    c->profiling = enable != 0;
+    return LCKV_OK;
+}
+
+int lckv_profile_read(lckv_cache *c, int32_t *n_launches, double *total_ms) {
+    if (!valid(c) || !n_launches || !total_ms) return LCKV_ERR_NULL;
+    if (hipDeviceSynchronize() != hipSuccess) return LCKV_ERR_HIP;
+    double sum = 0.0;
+    for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->ev[i], c->ev[i + 1]) != hipSuccess) return LCKV_ERR_HIP;
+        sum += ms;
+    }
+    *n_launches = (int32_t)(c->ev_used / 2);
+    *total_ms = sum;
+    c->ev_used = 0;
+    return LCKV_OK;
+}
+
+const char *lckv_strerror(int code) {
+    switch (code) {
+        case LCKV_OK: return "ok";
+        case LCKV_ERR_NULL: return "required pointer is NULL or handle is not a live lckv_cache";
+        case LCKV_ERR_CONFIG: return "unsupported or inconsistent configuration";
+        case LCKV_ERR_LAYER: return "layer or slot index out of range";
+        case LCKV_ERR_NOT_PRODUCER: return "no slot stores this layer's K/V";
+        case LCKV_ERR_BATCH: return "batch size or sequence index out of range";
+        case LCKV_ERR_LENGTH: return "length exceeds the cache capacity";
+        case LCKV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case LCKV_ERR_ALIGN: return "device pointer misaligned";
+        case LCKV_ERR_BLOCK_TABLE: return "block table missing or invalid";
+        case LCKV_ERR_HIP: return "HIP runtime call failed";
+        case LCKV_ERR_MASK: return "warmup mask differs from the cache's";
+        case LCKV_ERR_STORAGE: return "kv storage too small";
+        case LCKV_ERR_RANGE: return "position range outside the cache";
+        default: return "unknown lckv error";
+    }
+}
+
+}  // extern "C"

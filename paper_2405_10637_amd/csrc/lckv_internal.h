@@ -1,0 +1,104 @@
+// Internal declarations shared by the host API and the gfx950 kernels of liblckv.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/lckv.h"
+
+namespace lckv {
+
+constexpr int kPage = 16;        // positions per page
+constexpr int kMaxGroup = 16;    // query heads per kv head that fit one 16-column matrix tile
+
+// What a kernel needs to find a page pair of one slot.
+struct SlotView {
+    char *base;                 // first byte of the slot
+    const int32_t *table;       // paged: device block table [B_max][max_blocks], else nullptr
+    int32_t max_blocks;         // paged: table row length
+    int64_t num_blocks;         // paged: physical blocks per slot
+    int32_t pages_per_seq;      // contiguous: pages per (b, kv head)
+    int32_t Hkv;
+    int32_t page_bytes;         // bytes of one K (or V) page = 16 * D * elem
+    int32_t capacity;           // positions a sequence can hold
+};
+
+// Index of the page pair holding page p of (b, kv head g); -1 if the block table entry is invalid.
+__device__ __forceinline__ int64_t page_pair_index(const SlotView &v, int b, int g, int p) {
+    if (v.table) {
+        int32_t blk = v.table[(int64_t)b * v.max_blocks + p];
+        if (blk < 0 || (int64_t)blk >= v.num_blocks) return -1;
+        return (int64_t)blk * v.Hkv + g;
+    }
+    return ((int64_t)b * v.Hkv + g) * v.pages_per_seq + p;
+}
+
+// Element offsets inside a page (in elements, not bytes) for position j (0..15) and channel d.
+//
+// bf16 K page: [D/32][16 positions][32 channels]: one 16x32 operand tile of the QK matrix instruction per
+// 1 KiB; lane (j, kb) of a wave reads the 16 bytes at tile + j*64 + kb*16.
+__host__ __device__ __forceinline__ int k_elem_offset_bf16(int j, int d) {
+    return (d >> 5) * (kPage * 32) + j * 32 + (d & 31);
+}
+// bf16 V page: [D/32][16 channels r][4 position quads kb][2 channel blocks][4 positions]: lane (r, kb) reads
+// 16 bytes = positions 4kb..4kb+3 of channels (2*dp)*16 + r and (2*dp+1)*16 + r, the two 16x16 operand
+// tiles of the PV matrix instruction.
+__host__ __device__ __forceinline__ int v_elem_offset_bf16(int j, int d) {
+    int dblk = d >> 4, r = d & 15, dp = dblk >> 1, dsel = dblk & 1, kb = j >> 2, kq = j & 3;
+    return ((((dp * 16 + r) * 4 + kb) * 2 + dsel) * 4) + kq;
+}
+// fp32 pages are row-major [16][D].
+__host__ __device__ __forceinline__ int kv_elem_offset_f32(int j, int d, int D) { return j * D + d; }
+
+struct AttnParams {
+    SlotView slot;
+    const void *q;              // [B][Hq][D]
+    void *out;                  // [B][Hq][D]
+    const int32_t *seq_lens;    // [B]
+    float *part_o;              // [S][B][Hq][D] unnormalised partial outputs (S > 1)
+    float2 *part_ml;            // [S][B][Hq] (running max in log2 units, partial denominator)
+    int32_t *dev_err;
+    int32_t B, Hq, Hkv, G;
+    int32_t self_visible;       // 1: n_b = t_b + 1
+    int32_t max_n;              // clamp for n_b
+    int32_t split_tokens;       // keys per split (multiple of 16)
+    int32_t n_splits;
+    float scale_log2e;          // scale * log2(e)
+};
+
+hipError_t launch_attn_bf16(const AttnParams &p, int D, hipStream_t s);
+hipError_t launch_attn_f32(const AttnParams &p, int D, hipStream_t s);
+hipError_t launch_combine(const AttnParams &p, int D, int dtype, hipStream_t s);
+hipError_t launch_append(const SlotView &v, const void *k_new, const void *v_new, const int32_t *seq_lens,
+                         int B, int D, int dtype, int32_t *dev_err, hipStream_t s);
+hipError_t launch_bump(int32_t *seq_lens, int B, hipStream_t s);
+hipError_t launch_load_dense(const SlotView &v, const void *k, const void *vv, int B, int T, int D, int dtype,
+                             int32_t *dev_err, hipStream_t s);
+hipError_t launch_gather(const SlotView &v, int b, int pos, int n_pos, int D, int dtype, void *dev_k, void *dev_v,
+                         int32_t *dev_err, hipStream_t s);
+
+}  // namespace lckv
+
+struct lckv_cache {
+    uint64_t magic;
+    lckv_config cfg;
+    std::vector<uint8_t> warm;
+    std::vector<int32_t> kv_slot, self_visible, producer;  // pairing table
+    int32_t n_slots;
+    char *storage;
+    size_t slot_bytes;
+    int32_t pages_per_seq;
+    int32_t page_bytes;
+    const int32_t *table;
+    int32_t max_blocks;
+    int32_t capacity;
+    int32_t forced_split_tokens;
+    int32_t *dev_err;
+    float scale;
+    // kernel timing
+    bool profiling;
+    std::vector<hipEvent_t> ev;   // pairs (start, stop)
+    size_t ev_used;
+};
