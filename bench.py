@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the LCKV decode-attention step on one MI355X.
+
+A "step" is one lckv_step: for every layer, append of the new token's K/V where the layer produces a slot,
+split-KV attention of that layer's queries over the slot it is paired with, merge of the splits; then the length
+bump.  Inputs are synthetic and already resident in HBM when the timed region starts.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+METRIC = {
+    "C3": "decode attention tokens/s (all layers, Llama-7B shape, B=128, T=4096) + HBM GB/s %peak",
+}
+
+
+def cpu_baseline(sess, units, kv, q, k_new, v_new, out, target_cpu_s=12.0):
+    """Time the CPU oracle (as it stands) on a bounded sample of (layer, b, head) units of this workload, check the
+    GPU's output for those units against it, and extrapolate the sample's time to a whole step."""
+    import numpy as np
+    from oracle import lckv_oracle as orc
+
+    wl = sess.wl
+    G = wl.G
+    T = int(sess.lens0.max()) + 1
+    N = len(units)
+    Kb = np.zeros((N, T, wl.D), np.float32)
+    Vb = np.zeros((N, T, wl.D), np.float32)
+    qb = np.zeros((N, wl.D), np.float32)
+    nk = np.zeros(N, np.int64)
+    kn_h, vn_h, q_h = k_new.float().cpu().numpy(), v_new.float().cpu().numpy(), q.float().cpu().numpy()
+    for i, (l, b, h) in enumerate(units):
+        Ku, Vu = kv[(l, b, h)]
+        n = Ku.shape[0]
+        Kb[i, :n], Vb[i, :n] = Ku, Vu
+        slot, vis = sess.kv_slot[l]
+        if vis:  # a warmup layer also sees the token being decoded (Section 2.1)
+            Kb[i, n], Vb[i, n] = kn_h[slot, b, h // G], vn_h[slot, b, h // G]
+            n += 1
+        nk[i] = n
+        qb[i] = q_h[l, b, h]
+    scale = 1.0 / np.sqrt(wl.D)
+    t0 = time.perf_counter()
+    want, threads = orc.attend_many(qb, Kb, Vb, nk, scale)
+    dt = time.perf_counter() - t0
+    reps = 1
+    while dt * threads < target_cpu_s and reps < 16:   # repeat until roughly target_cpu_s core-seconds were spent
+        t0 = time.perf_counter()
+        orc.attend_many(qb, Kb, Vb, nk, scale)
+        dt = min(dt, time.perf_counter() - t0)
+        reps += 1
+    got = np.stack([out[l, b, h].float().cpu().numpy() for (l, b, h) in units]).astype(np.float64)
+    err = float(np.abs(got - want).max())
+    ref = float(np.abs(want).max())
+    total_visits = sess.kv_bytes_per_step(0) // (2 * wl.Hkv * wl.D * wl.elem_bytes) * G   # (query head, key) pairs
+    step_s = dt * (total_visits / float(nk.sum()))
+    return {
+        "value": wl.B / step_s, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+        "sample": "%d of %d (layer, sequence, head) units of the same step, best of %d runs, "
+                  "time scaled by key visits (%.3g s for the sample)" % (N, wl.L * wl.B * wl.Hq, reps, dt),
+        "max_abs_err_vs_gpu": err, "max_abs_expected": ref,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--split-tokens", type=int, default=0)
+    ap.add_argument("--sample", type=int, default=768, help="units the CPU oracle is timed and checked on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import numpy as np
+    import torch
+    from paper_2405_10637_amd import binding as lk
+    from paper_2405_10637_amd import synth
+    from paper_2405_10637_amd.runner import DecodeSession
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    lk.lib()  # fail loudly if the HIP library is not built
+    wl = synth.WORKLOADS[args.workload]
+    K, W = args.steps, args.warmup
+
+    sess = DecodeSession(wl, room=K + W + 2, split_tokens=args.split_tokens)
+    units = []
+    if not args.no_cpu_baseline:
+        warm_layers = [l for l in range(wl.L) if sess.kv_slot[l][1]]
+        units = synth.sample_units(wl, sess.lens0, args.sample, must_layers=warm_layers[:1] + warm_layers[-1:])
+    kv = sess.fill(units)
+    q, k_new, v_new = synth.step_inputs(wl, sess.n_slots, device="cuda")
+    out = torch.empty_like(q)
+
+    base = None
+    # first (untimed) step doubles as the check against the oracle
+    sess.step(q, k_new, v_new, out)
+    torch.cuda.synchronize()
+    if units:
+        base = cpu_baseline(sess, units, kv, q, k_new, v_new, out)
+        tol_ok = base["max_abs_err_vs_gpu"] <= 2e-2 and \
+            base["max_abs_err_vs_gpu"] <= 1e-2 * max(base["max_abs_expected"], 1e-3)
+        if wl.dtype == "f32":
+            tol_ok = base["max_abs_err_vs_gpu"] <= 1e-5
+        if not tol_ok:
+            sys.exit("GPU output disagrees with the oracle: %r" % base)
+    del kv
+    for _ in range(max(W - 1, 0)):
+        sess.step(q, k_new, v_new, out)
+    torch.cuda.synchronize()
+
+    lk.lckv_profile_read(sess.h)
+    lk.lckv_profile_enable(sess.h, True)
+    first_timed = 1 + max(W - 1, 0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        sess.step(q, k_new, v_new, out)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    n_launch, kern_ms = lk.lckv_profile_read(sess.h)
+    lk.lckv_profile_enable(sess.h, False)
+    assert lk.lckv_last_device_error(sess.h) == 0
+
+    ms_per_step = (t1 - t0) * 1e3 / K
+    kv_bytes = sum(sess.kv_bytes_per_step(first_timed + i) for i in range(K))
+    qo_bytes = K * 2 * wl.L * wl.B * wl.Hq * wl.D * wl.elem_bytes
+    alg_bytes_per_launch = (kv_bytes + qo_bytes) / float(K * wl.L)
+    avg_kernel_ms = kern_ms / max(n_launch, 1)
+    achieved = alg_bytes_per_launch / (avg_kernel_ms * 1e-3) / 1e9
+    step_gbps = (kv_bytes + qo_bytes) / K / (ms_per_step * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "attn_kernel_%s_hbm_traffic.txt" % args.workload)
+    if os.path.exists(tpath):   # bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
+
+    rec = {
+        "metric": METRIC.get(args.workload, "decode attention tokens/s (all layers, %s)" % wl.name),
+        "value": wl.B / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": "%s: L=%d w=%d Hq=%d Hkv=%d D=%d B=%d T=%s%s" % (
+            wl.name, wl.L, wl.w, wl.Hq, wl.Hkv, wl.D, wl.B,
+            wl.T if wl.T_min is None else "U[%d,%d]" % (wl.T_min, wl.T), " paged16" if wl.paged else ""),
+            "slots": sess.n_slots, "cache_GiB": round(sess.cache_bytes / 2 ** 30, 2)},
+        "step_effective_GBps": step_gbps, "step_pct_of_hbm_peak": 100.0 * step_gbps / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "attn_%s_kernel" % ("bf16" if wl.dtype == "bf16" else "f32"),
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": traffic, "launches": n_launch, "avg_launch_ms": avg_kernel_ms,
+                     "alg_bytes_per_launch": alg_bytes_per_launch},
+        "cpu_baseline": base,
+    }
+    sess.close()
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

@@ -138,10 +138,11 @@ int lckv_workspace_bytes(const lckv_cache *cache, int32_t B, int32_t max_len_hin
  * of a sequence's keys never depends on other sequences' lengths.  Host only; meant for tests and tuning. */
 int lckv_set_split_tokens(lckv_cache *cache, int32_t tokens);
 
-/* Bulk import (e.g. after prompt encoding): positions [0, T) of every sequence b < B of `slot` are written from
- * dense device tensors k, v of shape [B][T][Hkv][D].  Bits copied unchanged. */
-int lckv_cache_load_dense(lckv_cache *cache, int32_t slot, const void *k, const void *v, int32_t B, int32_t T,
-                          void *hip_stream);
+/* Bulk import (e.g. after prompt encoding): positions [0, min(T, t_b)) of every sequence b < B of `slot` are
+ * written from dense device tensors k, v of shape [B][T][Hkv][D]; dev_seq_lens (device int32[B]) may be NULL,
+ * then all T positions are written.  Bits copied unchanged. */
+int lckv_cache_load_dense(lckv_cache *cache, int32_t slot, const void *k, const void *v,
+                          const int32_t *dev_seq_lens, int32_t B, int32_t T, void *hip_stream);
 
 /* Logical read-back for tests and snapshots: positions [pos, pos + n_pos) of sequence b in `slot` are copied
  * to host_k, host_v as [n_pos][Hkv][D].  Allocates a temporary and SYNCHRONISES the device. */

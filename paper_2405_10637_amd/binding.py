@@ -71,7 +71,7 @@ def lib():
         L.lckv_step.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
         L.lckv_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
         L.lckv_set_split_tokens.argtypes = [vp, i32]
-        L.lckv_cache_load_dense.argtypes = [vp, i32, vp, vp, i32, i32, vp]
+        L.lckv_cache_load_dense.argtypes = [vp, i32, vp, vp, vp, i32, i32, vp]
         L.lckv_cache_read.argtypes = [vp, i32, i32, i32, i32, vp, vp]
         L.lckv_last_device_error.argtypes = [vp, ctypes.POINTER(i32)]
         L.lckv_profile_enable.argtypes = [vp, i32]
@@ -194,8 +194,9 @@ def lckv_set_split_tokens(cache: int, tokens: int):
     _check(lib().lckv_set_split_tokens(cache, tokens), "lckv_set_split_tokens")
 
 
-def lckv_cache_load_dense(cache: int, slot: int, k, v, B: int, T: int, stream=None):
-    _check(lib().lckv_cache_load_dense(cache, slot, _ptr(k), _ptr(v), B, T, _stream(stream)), "lckv_cache_load_dense")
+def lckv_cache_load_dense(cache: int, slot: int, k, v, dev_seq_lens, B: int, T: int, stream=None):
+    _check(lib().lckv_cache_load_dense(cache, slot, _ptr(k), _ptr(v), _ptr(dev_seq_lens), B, T, _stream(stream)),
+           "lckv_cache_load_dense")
 
 
 def lckv_cache_read(cache: int, slot: int, b: int, pos: int, n_pos: int, host_k: np.ndarray, host_v: np.ndarray):

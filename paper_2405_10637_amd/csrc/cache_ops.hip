@@ -52,26 +52,36 @@ __global__ void append_kernel(SlotView sv, const E *k_new, const E *v_new, const
     vpage[v_off<E>(j, d, D)] = v_new[i];
 }
 
-// Dense [B][T][Hkv][D] -> cache, positions [0, T).  One thread per element.
+// Dense [B][T][Hkv][D] -> cache, positions [0, min(T, lens[b])).  One thread per 16-byte chunk of the dense
+// tensors, grid-stride (a launch may not exceed 2^32 threads, and the big caches hold more elements than that).
 template <typename E>
-__global__ void load_dense_kernel(SlotView sv, const E *k, const E *v, int B, int T, int D, int32_t *dev_err) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t total = (int64_t)B * T * sv.Hkv * D;
-    if (i >= total) return;
-    int d = (int)(i % D);
-    int g = (int)((i / D) % sv.Hkv);
-    int t = (int)((i / ((int64_t)D * sv.Hkv)) % T);
-    int b = (int)(i / ((int64_t)D * sv.Hkv * T));
-    int64_t idx = page_pair_index(sv, b, g, t / kPage);
-    if (idx < 0) {
-        if (d == 0) atomicOr(dev_err, LCKV_DEV_ERR_BLOCK);
-        return;
+__global__ void load_dense_kernel(SlotView sv, const E *k, const E *v, const int32_t *lens, int B, int T, int D,
+                                  int32_t *dev_err) {
+    constexpr int C = 16 / (int)sizeof(E);  // elements per chunk
+    const int chunks = D / C;
+    const int64_t total = (int64_t)B * T * sv.Hkv * chunks;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        int dc = (int)(i % chunks);
+        int g = (int)((i / chunks) % sv.Hkv);
+        int t = (int)((i / ((int64_t)chunks * sv.Hkv)) % T);
+        int b = (int)(i / ((int64_t)chunks * sv.Hkv * T));
+        if (lens && t >= lens[b]) continue;
+        int64_t idx = page_pair_index(sv, b, g, t / kPage);
+        if (idx < 0) {
+            if (dc == 0) atomicOr(dev_err, LCKV_DEV_ERR_BLOCK);
+            continue;
+        }
+        E *kpage = (E *)(sv.base + idx * (2 * (int64_t)sv.page_bytes));
+        E *vpage = (E *)((char *)kpage + sv.page_bytes);
+        int j = t % kPage;
+        const E *ks = k + i * C, *vs = v + i * C;
+#pragma unroll
+        for (int e = 0; e < C; ++e) {
+            kpage[k_off<E>(j, dc * C + e, D)] = ks[e];
+            vpage[v_off<E>(j, dc * C + e, D)] = vs[e];
+        }
     }
-    E *kpage = (E *)(sv.base + idx * (2 * (int64_t)sv.page_bytes));
-    E *vpage = (E *)((char *)kpage + sv.page_bytes);
-    int j = t % kPage;
-    kpage[k_off<E>(j, d, D)] = k[i];
-    vpage[v_off<E>(j, d, D)] = v[i];
 }
 
 // cache -> dense [n_pos][Hkv][D] for one sequence
@@ -152,16 +162,18 @@ hipError_t launch_bump(int32_t *seq_lens, int B, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_load_dense(const SlotView &v, const void *k, const void *vv, int B, int T, int D, int dtype,
-                             int32_t *dev_err, hipStream_t s) {
-    int64_t total = (int64_t)B * T * v.Hkv * D;
+hipError_t launch_load_dense(const SlotView &v, const void *k, const void *vv, const int32_t *lens, int B, int T,
+                             int D, int dtype, int32_t *dev_err, hipStream_t s) {
+    int64_t total = (int64_t)B * T * v.Hkv * (D * (dtype == LCKV_BF16 ? 2 : 4) / 16);
     if (total == 0) return hipSuccess;
+    int64_t nb = (total + 255) / 256;
+    if (nb > (1 << 22)) nb = 1 << 22;  // grid-stride beyond this
     if (dtype == LCKV_BF16)
-        hipLaunchKernelGGL(load_dense_kernel<uint16_t>, dim3(blocks_for(total, 256)), dim3(256), 0, s, v,
-                           (const uint16_t *)k, (const uint16_t *)vv, B, T, D, dev_err);
+        hipLaunchKernelGGL(load_dense_kernel<uint16_t>, dim3((unsigned)nb), dim3(256), 0, s, v,
+                           (const uint16_t *)k, (const uint16_t *)vv, lens, B, T, D, dev_err);
     else
-        hipLaunchKernelGGL(load_dense_kernel<uint32_t>, dim3(blocks_for(total, 256)), dim3(256), 0, s, v,
-                           (const uint32_t *)k, (const uint32_t *)vv, B, T, D, dev_err);
+        hipLaunchKernelGGL(load_dense_kernel<uint32_t>, dim3((unsigned)nb), dim3(256), 0, s, v,
+                           (const uint32_t *)k, (const uint32_t *)vv, lens, B, T, D, dev_err);
     return hipGetLastError();
 }
 

@@ -29,6 +29,8 @@ int check_config(const lckv_config *cfg) {
     if (cfg->D != 64 && cfg->D != 128) return LCKV_ERR_CONFIG;
     if (cfg->dtype != LCKV_BF16 && cfg->dtype != LCKV_F32) return LCKV_ERR_CONFIG;
     if (cfg->B_max < 1 || cfg->B_max > 65535) return LCKV_ERR_CONFIG;
+    // one thread per output element in the small kernels: a launch holds fewer than 2^32 threads
+    if ((int64_t)cfg->B_max * cfg->Hq * cfg->D >= ((int64_t)1 << 31)) return LCKV_ERR_CONFIG;
     if (cfg->page_size != 0 && cfg->page_size != kPage) return LCKV_ERR_CONFIG;
     if (cfg->page_size == 0 && (cfg->T_max < 1 || cfg->T_max > (1 << 24))) return LCKV_ERR_CONFIG;
     if (cfg->page_size == kPage && (cfg->num_blocks < 1 || cfg->num_blocks > (int64_t)1 << 31)) return LCKV_ERR_CONFIG;
@@ -355,15 +357,15 @@ int lckv_set_split_tokens(lckv_cache *c, int32_t tokens) {
     return LCKV_OK;
 }
 
-int lckv_cache_load_dense(lckv_cache *c, int32_t slot, const void *k, const void *v, int32_t B, int32_t T,
-                          void *hip_stream) {
+int lckv_cache_load_dense(lckv_cache *c, int32_t slot, const void *k, const void *v, const int32_t *dev_seq_lens,
+                          int32_t B, int32_t T, void *hip_stream) {
     if (!valid(c) || !k || !v) return LCKV_ERR_NULL;
     if (slot < 0 || slot >= c->n_slots) return LCKV_ERR_LAYER;
     if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
     if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
     if (T < 0 || T > c->capacity) return LCKV_ERR_LENGTH;
-    hipError_t e = launch_load_dense(slot_view(c, slot), k, v, B, T, c->cfg.D, c->cfg.dtype, c->dev_err,
-                                     (hipStream_t)hip_stream);
+    hipError_t e = launch_load_dense(slot_view(c, slot), k, v, dev_seq_lens, B, T, c->cfg.D, c->cfg.dtype,
+                                     c->dev_err, (hipStream_t)hip_stream);
     return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
 }
 
@@ -373,6 +375,7 @@ int lckv_cache_read(lckv_cache *c, int32_t slot, int32_t b, int32_t pos, int32_t
     if (b < 0 || b >= c->cfg.B_max) return LCKV_ERR_BATCH;
     if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
     if (pos < 0 || n_pos < 1 || (int64_t)pos + n_pos > c->capacity) return LCKV_ERR_RANGE;
+    if ((int64_t)n_pos * c->cfg.Hkv * c->cfg.D >= ((int64_t)1 << 31)) return LCKV_ERR_RANGE;
     size_t bytes = (size_t)n_pos * c->cfg.Hkv * c->cfg.D * elem_bytes(c->cfg.dtype);
     char *tmp = nullptr;
     if (hipMalloc((void **)&tmp, 2 * bytes) != hipSuccess) return LCKV_ERR_HIP;

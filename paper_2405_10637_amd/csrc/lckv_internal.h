@@ -74,7 +74,8 @@ hipError_t launch_combine(const AttnParams &p, int D, int dtype, hipStream_t s);
 hipError_t launch_append(const SlotView &v, const void *k_new, const void *v_new, const int32_t *seq_lens,
                          int B, int D, int dtype, int32_t *dev_err, hipStream_t s);
 hipError_t launch_bump(int32_t *seq_lens, int B, hipStream_t s);
-hipError_t launch_load_dense(const SlotView &v, const void *k, const void *vv, int B, int T, int D, int dtype,
+hipError_t launch_load_dense(const SlotView &v, const void *k, const void *vv, const int32_t *lens, int B, int T,
+                             int D, int dtype,
                              int32_t *dev_err, hipStream_t s);
 hipError_t launch_gather(const SlotView &v, int b, int pos, int n_pos, int D, int dtype, void *dev_k, void *dev_v,
                          int32_t *dev_err, hipStream_t s);

@@ -81,7 +81,7 @@ class GpuCache:
         """K, V: [B][T][Hkv][D] tensors (any device) in the cache dtype."""
         K = K.to(DEV).contiguous()
         V = V.to(DEV).contiguous()
-        lk.lckv_cache_load_dense(self.h, slot, K, V, K.shape[0], K.shape[1])
+        lk.lckv_cache_load_dense(self.h, slot, K, V, None, K.shape[0], K.shape[1])
         torch.cuda.synchronize()
 
     def step(self, q, k_new, v_new, max_len_hint=None):
