@@ -79,6 +79,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--split-tokens", type=int, default=0)
+    ap.add_argument("--load-policy", type=int, default=0, help="0 auto, 1 plain loads, 2 nontemporal loads")
     ap.add_argument("--sample", type=int, default=768, help="units the CPU oracle is timed and checked on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -98,6 +99,7 @@ def main():
     K, W = args.steps, args.warmup
 
     sess = DecodeSession(wl, room=K + W + 2, split_tokens=args.split_tokens)
+    lk.lckv_set_load_policy(sess.h, args.load_policy)
     units = []
     if not args.no_cpu_baseline:
         warm_layers = [l for l in range(wl.L) if sess.kv_slot[l][1]]
@@ -136,6 +138,18 @@ def main():
     lk.lckv_profile_enable(sess.h, False)
     assert lk.lckv_last_device_error(sess.h) == 0
 
+    # what a pure read with the same load pattern reaches on this device (context for the roofline fraction)
+    probe_bytes = min(sess.cache_bytes, 16 << 30) // (2 << 20) * (2 << 20)
+    lk.lckv_hbm_read_probe(sess.h, sess.storage, probe_bytes, True)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(3):
+        lk.lckv_hbm_read_probe(sess.h, sess.storage, probe_bytes, True)
+    e1.record()
+    torch.cuda.synchronize()
+    probe_gbps = 3 * probe_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
     ms_per_step = (t1 - t0) * 1e3 / K
     kv_bytes = sum(sess.kv_bytes_per_step(first_timed + i) for i in range(K))
     qo_bytes = K * 2 * wl.L * wl.B * wl.Hq * wl.D * wl.elem_bytes
@@ -161,6 +175,7 @@ def main():
             wl.T if wl.T_min is None else "U[%d,%d]" % (wl.T_min, wl.T), " paged16" if wl.paged else ""),
             "slots": sess.n_slots, "cache_GiB": round(sess.cache_bytes / 2 ** 30, 2)},
         "step_effective_GBps": step_gbps, "step_pct_of_hbm_peak": 100.0 * step_gbps / HBM_PEAK_GBPS,
+        "read_probe_GBps": probe_gbps,
         "roofline": {"bound": "hbm", "kernel": "attn_%s_kernel" % ("bf16" if wl.dtype == "bf16" else "f32"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": traffic, "launches": n_launch, "avg_launch_ms": avg_kernel_ms,

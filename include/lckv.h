@@ -138,6 +138,14 @@ int lckv_workspace_bytes(const lckv_cache *cache, int32_t B, int32_t max_len_hin
  * of a sequence's keys never depends on other sequences' lengths.  Host only; meant for tests and tuning. */
 int lckv_set_split_tokens(lckv_cache *cache, int32_t tokens);
 
+/* How the attention kernels read K/V: AUTO uses the nontemporal hint when one layer's pass over its slot is
+ * larger than the 256 MB last-level cache (nothing of it would survive until the next layer's pass), plain loads
+ * otherwise (a small shared slot is re-read by every condensed layer and may stay cached).  Host only. */
+#define LCKV_LOAD_AUTO 0
+#define LCKV_LOAD_TEMPORAL 1
+#define LCKV_LOAD_NONTEMPORAL 2
+int lckv_set_load_policy(lckv_cache *cache, int32_t policy);
+
 /* Bulk import (e.g. after prompt encoding): positions [0, min(T, t_b)) of every sequence b < B of `slot` are
  * written from dense device tensors k, v of shape [B][T][Hkv][D]; dev_seq_lens (device int32[B]) may be NULL,
  * then all T positions are written.  Bits copied unchanged. */
@@ -157,6 +165,11 @@ int lckv_last_device_error(lckv_cache *cache, int32_t *bits);
  * timed launches and their summed duration since the last read, and resets both. */
 int lckv_profile_enable(lckv_cache *cache, int32_t enable);
 int lckv_profile_read(lckv_cache *cache, int32_t *n_launches, double *total_ms);
+
+/* Measurement aid: read `bytes` (a multiple of 2 MiB is read, the rest ignored) of device memory with the
+ * attention kernel's load pattern (with or without the nontemporal hint) and discard them; timing it gives the
+ * read bandwidth reachable on the device at hand, to set beside the published peak.  Only enqueues. */
+int lckv_hbm_read_probe(lckv_cache *cache, const void *dev_buf, size_t bytes, int32_t nontemporal, void *hip_stream);
 
 const char *lckv_strerror(int code);
 

@@ -21,12 +21,13 @@ LCKV_ERR_MASK, LCKV_ERR_STORAGE, LCKV_ERR_RANGE = -11, -12, -13
 LCKV_BF16, LCKV_F32 = 0, 1
 LCKV_PAIR_TOP_OF_CONDENSED, LCKV_PAIR_LAST_LAYER = 0, 1
 LCKV_DEV_ERR_CAPACITY, LCKV_DEV_ERR_BLOCK = 1, 2
+LCKV_LOAD_AUTO, LCKV_LOAD_TEMPORAL, LCKV_LOAD_NONTEMPORAL = 0, 1, 2
 
 EXPORTS = [
     "lckv_cache_bytes", "lckv_cache_alloc", "lckv_cache_free", "lckv_cache_set_block_table", "lckv_n_slots",
     "lckv_kv_slot", "lckv_slot_producer", "lckv_append_kv", "lckv_decode_attention", "lckv_step",
-    "lckv_workspace_bytes", "lckv_set_split_tokens", "lckv_cache_load_dense", "lckv_cache_read",
-    "lckv_last_device_error", "lckv_profile_enable", "lckv_profile_read", "lckv_strerror",
+    "lckv_workspace_bytes", "lckv_set_split_tokens", "lckv_set_load_policy", "lckv_cache_load_dense", "lckv_cache_read",
+    "lckv_last_device_error", "lckv_profile_enable", "lckv_profile_read", "lckv_hbm_read_probe", "lckv_strerror",
 ]
 
 
@@ -71,11 +72,13 @@ def lib():
         L.lckv_step.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
         L.lckv_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
         L.lckv_set_split_tokens.argtypes = [vp, i32]
+        L.lckv_set_load_policy.argtypes = [vp, i32]
         L.lckv_cache_load_dense.argtypes = [vp, i32, vp, vp, vp, i32, i32, vp]
         L.lckv_cache_read.argtypes = [vp, i32, i32, i32, i32, vp, vp]
         L.lckv_last_device_error.argtypes = [vp, ctypes.POINTER(i32)]
         L.lckv_profile_enable.argtypes = [vp, i32]
         L.lckv_profile_read.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double)]
+        L.lckv_hbm_read_probe.argtypes = [vp, vp, sz, i32, vp]
         L.lckv_strerror.argtypes = [ctypes.c_int]
         L.lckv_strerror.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -194,6 +197,10 @@ def lckv_set_split_tokens(cache: int, tokens: int):
     _check(lib().lckv_set_split_tokens(cache, tokens), "lckv_set_split_tokens")
 
 
+def lckv_set_load_policy(cache: int, policy: int):
+    _check(lib().lckv_set_load_policy(cache, policy), "lckv_set_load_policy")
+
+
 def lckv_cache_load_dense(cache: int, slot: int, k, v, dev_seq_lens, B: int, T: int, stream=None):
     _check(lib().lckv_cache_load_dense(cache, slot, _ptr(k), _ptr(v), _ptr(dev_seq_lens), B, T, _stream(stream)),
            "lckv_cache_load_dense")
@@ -208,6 +215,11 @@ def lckv_last_device_error(cache: int) -> int:
     bits = ctypes.c_int32(0)
     _check(lib().lckv_last_device_error(cache, ctypes.byref(bits)), "lckv_last_device_error")
     return bits.value
+
+
+def lckv_hbm_read_probe(cache: int, dev_buf, nbytes: int, nontemporal: bool = True, stream=None):
+    _check(lib().lckv_hbm_read_probe(cache, _ptr(dev_buf), nbytes, int(nontemporal), _stream(stream)),
+           "lckv_hbm_read_probe")
 
 
 def lckv_profile_enable(cache: int, enable: bool):

@@ -14,6 +14,7 @@ constexpr uint64_t kMagic = 0x4c434b5643414348ull;  // "LCKVCACH"
 constexpr size_t kProfilePairs = 4096;
 constexpr int kTargetWorkgroups = 2048;  // 8 per compute unit: enough to hide the tail of the last wave of groups
 constexpr int kMinSplitTokens = 256;
+constexpr double kLastLevelCacheBytes = 256.0 * 1024 * 1024;  // MI355X Infinity Cache
 
 bool valid(const lckv_cache *c) { return c && c->magic == kMagic; }
 
@@ -163,6 +164,11 @@ int attention_impl(lckv_cache *c, int layer, const void *q, void *out, const int
     p.split_tokens = sp.tokens;
     p.n_splits = sp.n_splits;
     p.scale_log2e = c->scale * 1.4426950408889634f;
+    // K/V of one layer's pass: B * n * 2 * Hkv * D * elem bytes.  Past the size of the last-level cache nothing
+    // of it survives until the next layer reads the slot again, and the nontemporal hint makes the stream faster.
+    const double pass_bytes = (double)B * max_n * 2.0 * cfg.Hkv * cfg.D * elem_bytes(cfg.dtype);
+    p.nontemporal = c->load_policy == LCKV_LOAD_NONTEMPORAL ||
+                    (c->load_policy == LCKV_LOAD_AUTO && pass_bytes > kLastLevelCacheBytes);
 
     const bool timed = c->profiling && c->ev_used + 2 <= c->ev.size();
     if (timed && hipEventRecord(c->ev[c->ev_used], stream) != hipSuccess) return LCKV_ERR_HIP;
@@ -222,6 +228,7 @@ int lckv_cache_alloc(const lckv_config *cfg, void *kv_storage, size_t kv_bytes, 
     c->max_blocks = 0;
     c->capacity = cfg->page_size ? 0 : g.pages_per_seq * kPage;
     c->forced_split_tokens = 0;
+    c->load_policy = LCKV_LOAD_AUTO;
     c->scale = cfg->scale > 0.f ? cfg->scale : 1.0f / sqrtf((float)cfg->D);
     c->profiling = false;
     c->ev_used = 0;
@@ -357,6 +364,14 @@ int lckv_set_split_tokens(lckv_cache *c, int32_t tokens) {
     return LCKV_OK;
 }
 
+int lckv_set_load_policy(lckv_cache *c, int32_t policy) {
+    if (!valid(c)) return LCKV_ERR_NULL;
+    if (policy != LCKV_LOAD_AUTO && policy != LCKV_LOAD_TEMPORAL && policy != LCKV_LOAD_NONTEMPORAL)
+        return LCKV_ERR_CONFIG;
+    c->load_policy = policy;
+    return LCKV_OK;
+}
+
 int lckv_cache_load_dense(lckv_cache *c, int32_t slot, const void *k, const void *v, const int32_t *dev_seq_lens,
                           int32_t B, int32_t T, void *hip_stream) {
     if (!valid(c) || !k || !v) return LCKV_ERR_NULL;
@@ -424,6 +439,13 @@ int lckv_profile_read(lckv_cache *c, int32_t *n_launches, double *total_ms) {
     *total_ms = sum;
     c->ev_used = 0;
     return LCKV_OK;
+}
+
+int lckv_hbm_read_probe(lckv_cache *c, const void *dev_buf, size_t bytes, int32_t nontemporal, void *hip_stream) {
+    if (!valid(c) || !dev_buf) return LCKV_ERR_NULL;
+    if (!aligned(dev_buf, 16)) return LCKV_ERR_ALIGN;
+    hipError_t e = launch_stream_probe(dev_buf, bytes, nontemporal, c->dev_err + 1, (hipStream_t)hip_stream);
+    return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
 }
 
 const char *lckv_strerror(int code) {

@@ -35,19 +35,21 @@ __device__ __forceinline__ int64_t page_pair_index(const SlotView &v, int b, int
     return ((int64_t)b * v.Hkv + g) * v.pages_per_seq + p;
 }
 
-// Element offsets inside a page (in elements, not bytes) for position j (0..15) and channel d.
+// Element offsets inside a page (in elements, not bytes) for position j (0..15) and channel d.  bf16 pages are
+// stored in matrix-operand order: the 16 bytes lane l of a wave feeds to the matrix instruction sit at byte
+// l*16 of a 1 KiB tile, so a wave's load is one contiguous, lane-ordered KiB.
 //
-// bf16 K page: [D/32][16 positions][32 channels]: one 16x32 operand tile of the QK matrix instruction per
-// 1 KiB; lane (j, kb) of a wave reads the 16 bytes at tile + j*64 + kb*16.
+// bf16 K page: [D/32 tiles][4 channel octets kb][16 positions j][8 channels]: tile ks is the 16x32 A operand of
+// the QK instruction for channels 32ks..32ks+31; lane kb*16 + j holds channels 32ks + 8kb .. +8 of position j.
 __host__ __device__ __forceinline__ int k_elem_offset_bf16(int j, int d) {
-    return (d >> 5) * (kPage * 32) + j * 32 + (d & 31);
+    return (((d >> 5) * 4 + ((d & 31) >> 3)) * kPage + j) * 8 + (d & 7);
 }
-// bf16 V page: [D/32][16 channels r][4 position quads kb][2 channel blocks][4 positions]: lane (r, kb) reads
-// 16 bytes = positions 4kb..4kb+3 of channels (2*dp)*16 + r and (2*dp+1)*16 + r, the two 16x16 operand
-// tiles of the PV matrix instruction.
+// bf16 V page: [D/32 tiles][4 position quads kb][16 channels r][2 channel blocks][4 positions]: lane kb*16 + r
+// holds positions 4kb..4kb+3 of channels (2dp)*16 + r and (2dp+1)*16 + r, the A operands of two 16x16x16 PV
+// instructions.
 __host__ __device__ __forceinline__ int v_elem_offset_bf16(int j, int d) {
     int dblk = d >> 4, r = d & 15, dp = dblk >> 1, dsel = dblk & 1, kb = j >> 2, kq = j & 3;
-    return ((((dp * 16 + r) * 4 + kb) * 2 + dsel) * 4) + kq;
+    return ((((dp * 4 + kb) * 16 + r) * 2 + dsel) * 4) + kq;
 }
 // fp32 pages are row-major [16][D].
 __host__ __device__ __forceinline__ int kv_elem_offset_f32(int j, int d, int D) { return j * D + d; }
@@ -66,6 +68,7 @@ struct AttnParams {
     int32_t split_tokens;       // keys per split (multiple of 16)
     int32_t n_splits;
     float scale_log2e;          // scale * log2(e)
+    int32_t nontemporal;        // 1: read K/V with the nontemporal hint (stream larger than the caches)
 };
 
 hipError_t launch_attn_bf16(const AttnParams &p, int D, hipStream_t s);
@@ -77,6 +80,7 @@ hipError_t launch_bump(int32_t *seq_lens, int B, hipStream_t s);
 hipError_t launch_load_dense(const SlotView &v, const void *k, const void *vv, const int32_t *lens, int B, int T,
                              int D, int dtype,
                              int32_t *dev_err, hipStream_t s);
+hipError_t launch_stream_probe(const void *buf, size_t bytes, int nontemporal, int32_t *sink, hipStream_t s);
 hipError_t launch_gather(const SlotView &v, int b, int pos, int n_pos, int D, int dtype, void *dev_k, void *dev_v,
                          int32_t *dev_err, hipStream_t s);
 
@@ -96,6 +100,7 @@ struct lckv_cache {
     int32_t max_blocks;
     int32_t capacity;
     int32_t forced_split_tokens;
+    int32_t load_policy;          // LCKV_LOAD_*
     int32_t *dev_err;
     float scale;
     // kernel timing

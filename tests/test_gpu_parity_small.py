@@ -193,6 +193,23 @@ def test_condensed_layers_with_equal_queries_give_bitwise_equal_outputs_and_batc
     assert torch.equal(outs[0][:, perm], outs[1])                                        # bitwise
 
 
+def test_load_policy_does_not_change_a_bit():
+    # plain and nontemporal loads read the same bytes: outputs must be bitwise equal, contiguous and paged
+    for paged in (False, True):
+        wl = synth.Workload("t-policy", "bf16", L=3, w=1, Hq=8, Hkv=4, D=128, B=3, T=260, sigma=1.0, seed=25,
+                            paged=paged)
+        lens = np.array([260, 33, 128], np.int32)
+        K, V = synth.logical_cache(wl, 2, 260)
+        q, kn, vn = synth.step_inputs(wl, 2)
+        outs = []
+        for policy in (lk.LCKV_LOAD_TEMPORAL, lk.LCKV_LOAD_NONTEMPORAL):
+            with GpuCache(wl, 272, lens, split_tokens=64, load_policy=policy) as gc:
+                for s in range(2):
+                    gc.load_dense(s, K[s], V[s])
+                outs.append(gc.step(q, kn, vn).cpu())
+        assert torch.equal(outs[0], outs[1]) and torch.isfinite(outs[0].float()).all()
+
+
 def test_new_shared_kv_is_invisible_now_and_visible_next_step():
     # Section 2.1 (diagonal mask): the K/V appended to the shared slot this step change no condensed output
     # this step and change them at the next step.
