@@ -25,7 +25,6 @@ typedef __attribute__((ext_vector_type(4))) short shortx4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
-constexpr int kWaves = 4;
 constexpr float kNegInf = -__builtin_huge_valf();
 
 __device__ __forceinline__ float xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask, 64)); }
@@ -160,8 +159,9 @@ __device__ __forceinline__ void consume_tile(Tile<D, NP> &t, const bf16x8 (&qb)[
     }
 }
 
-template <int D, int NP, bool PAGED, bool NT>
-__global__ __launch_bounds__(kWaves * 64) void attn_bf16_kernel(AttnParams p) {
+// W waves per workgroup, NP pages (of 16 keys) per wave and tile.
+template <int D, int NP, int W, bool PAGED, bool NT>
+__global__ __launch_bounds__(W * 64) void attn_bf16_kernel(AttnParams p) {
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: page numbers stay uniform
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kWaves * 64) void attn_bf16_kernel(AttnParams p) {
         if (p.n_splits == 1) {
             // no visible key at all: the zero vector (zero dummy K/V of the first token, Section 2.1)
             uint16_t *o = (uint16_t *)p.out + ((int64_t)b * p.Hq + (int64_t)g * G) * D;
-            for (int i = tid; i < G * D; i += kWaves * 64) o[i] = 0;
+            for (int i = tid; i < G * D; i += W * 64) o[i] = 0;
         } else if (tid < G) {
             p.part_ml[((int64_t)split * p.B + b) * p.Hq + g * G + tid] = float2{kNegInf, 0.f};
         }
@@ -209,7 +209,7 @@ __global__ __launch_bounds__(kWaves * 64) void attn_bf16_kernel(AttnParams p) {
     const float cs = p.scale_log2e;
     const int lane_off = lane * 16;
     const int pg_end = (k_end + kPage - 1) / kPage;
-    constexpr int kStride = kWaves * NP;
+    constexpr int kStride = W * NP;
 
     // two tiles in flight per wave: the loads of the next tile are issued before the current one is used
     int pg = k_begin / kPage + wave * NP;
@@ -230,9 +230,9 @@ __global__ __launch_bounds__(kWaves * 64) void attn_bf16_kernel(AttnParams p) {
     l += __shfl_xor(l, 32, 64);
 
     // merge the four waves: (m, l, O) per query column through LDS
-    __shared__ float sm_m[kWaves][16];
-    __shared__ float sm_l[kWaves][16];
-    __shared__ floatx4 sm_acc[kWaves][D / 16][64];
+    __shared__ float sm_m[W][16];
+    __shared__ float sm_l[W][16];
+    __shared__ floatx4 sm_acc[W][D / 16][64];
     if (kb == 0) {
         sm_m[wave][c] = m * cs;  // log2 units; -inf for a wave that saw no page
         sm_l[wave][c] = l;
@@ -243,19 +243,19 @@ __global__ __launch_bounds__(kWaves * 64) void attn_bf16_kernel(AttnParams p) {
 
     float M = kNegInf;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sm_m[w][c]);
-    float f[kWaves], L = 0.f;
+    for (int w = 0; w < W; ++w) M = fmaxf(M, sm_m[w][c]);
+    float f[W], L = 0.f;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
+    for (int w = 0; w < W; ++w) {
         float mw = sm_m[w][c];
         f[w] = (mw == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
         L += f[w] * sm_l[w][c];
     }
     // wave w finishes channel tiles w, w + 4, ...
-    for (int j = wave; j < D / 16; j += kWaves) {
+    for (int j = wave; j < D / 16; j += W) {
         floatx4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w)
+        for (int w = 0; w < W; ++w)
             if (f[w] != 0.f) o += f[w] * sm_acc[w][j][lane];
         if (c < G) {
             int d0 = j * 16 + 4 * kb;  // this lane holds channels d0..d0+3 of query head h
@@ -272,25 +272,27 @@ __global__ __launch_bounds__(kWaves * 64) void attn_bf16_kernel(AttnParams p) {
         p.part_ml[((int64_t)split * p.B + b) * p.Hq + h] = float2{M, L};
 }
 
-template <int D, int NP>
+template <int D, int NP, int W>
 static hipError_t launch_variant(const AttnParams &p, hipStream_t s) {
-    dim3 grid(p.n_splits, p.Hkv, p.B), block(kWaves * 64);
+    dim3 grid(p.n_splits, p.Hkv, p.B), block(W * 64);
     if (p.slot.table) {
         if (p.nontemporal)
-            hipLaunchKernelGGL((attn_bf16_kernel<D, NP, true, true>), grid, block, 0, s, p);
+            hipLaunchKernelGGL((attn_bf16_kernel<D, NP, W, true, true>), grid, block, 0, s, p);
         else
-            hipLaunchKernelGGL((attn_bf16_kernel<D, NP, true, false>), grid, block, 0, s, p);
+            hipLaunchKernelGGL((attn_bf16_kernel<D, NP, W, true, false>), grid, block, 0, s, p);
     } else {
         if (p.nontemporal)
-            hipLaunchKernelGGL((attn_bf16_kernel<D, NP, false, true>), grid, block, 0, s, p);
+            hipLaunchKernelGGL((attn_bf16_kernel<D, NP, W, false, true>), grid, block, 0, s, p);
         else
-            hipLaunchKernelGGL((attn_bf16_kernel<D, NP, false, false>), grid, block, 0, s, p);
+            hipLaunchKernelGGL((attn_bf16_kernel<D, NP, W, false, false>), grid, block, 0, s, p);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_attn_bf16(const AttnParams &p, int D, hipStream_t s) {
-    return D == 128 ? launch_variant<128, 2>(p, s) : launch_variant<64, 2>(p, s);
+    // One page per wave and tile: measured fastest on MI355X for the Llama-7B shape (three waves per SIMD fit in
+    // the register file; two- and four-page tiles were 1-2 % slower).
+    return D == 128 ? launch_variant<128, 1, 4>(p, s) : launch_variant<64, 1, 4>(p, s);
 }
 
 // Measurement aid: stream `bytes` of device memory through the same access pattern the attention kernel uses
