@@ -82,6 +82,8 @@ def main():
     ap.add_argument("--load-policy", type=int, default=0, help="0 auto, 1 plain loads, 2 nontemporal loads")
     ap.add_argument("--sample", type=int, default=768, help="units the CPU oracle is timed and checked on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one lckv_step in a HIP graph (length bound = last timed step) and time replays")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -98,7 +100,7 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     K, W = args.steps, args.warmup
 
-    sess = DecodeSession(wl, room=K + W + 2, split_tokens=args.split_tokens)
+    sess = DecodeSession(wl, room=2 * K + W + 2, split_tokens=args.split_tokens)
     lk.lckv_set_load_policy(sess.h, args.load_policy)
     units = []
     if not args.no_cpu_baseline:
@@ -125,15 +127,31 @@ def main():
         sess.step(q, k_new, v_new, out)
     torch.cuda.synchronize()
 
+    first_timed = 1 + max(W - 1, 0)
+    if args.graph:
+        # One captured step replayed K times; the per-launch events are taken in a second, eager pass of K steps.
+        hint = sess.max_len + 2 * K
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            lk.lckv_step(sess.h, q, k_new, v_new, out, sess.lens, wl.B, hint, sess.workspace)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        sess.max_len += K
+        sess.steps_left -= K
     lk.lckv_profile_read(sess.h)
     lk.lckv_profile_enable(sess.h, True)
-    first_timed = 1 + max(W - 1, 0)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(K):
+    te0 = time.perf_counter()
+    for _ in range(0 if args.graph and sess.steps_left < K else K):
         sess.step(q, k_new, v_new, out)
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    te1 = time.perf_counter()
+    if not args.graph:
+        t0, t1 = te0, te1
     n_launch, kern_ms = lk.lckv_profile_read(sess.h)
     lk.lckv_profile_enable(sess.h, False)
     assert lk.lckv_last_device_error(sess.h) == 0
@@ -153,7 +171,9 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / K
     kv_bytes = sum(sess.kv_bytes_per_step(first_timed + i) for i in range(K))
     qo_bytes = K * 2 * wl.L * wl.B * wl.Hq * wl.D * wl.elem_bytes
-    alg_bytes_per_launch = (kv_bytes + qo_bytes) / float(K * wl.L)
+    ev_first = first_timed + (K if args.graph else 0)   # the steps whose launches carried the events
+    ev_bytes = sum(sess.kv_bytes_per_step(ev_first + i) for i in range(K)) + qo_bytes
+    alg_bytes_per_launch = ev_bytes / float(K * wl.L)
     avg_kernel_ms = kern_ms / max(n_launch, 1)
     achieved = alg_bytes_per_launch / (avg_kernel_ms * 1e-3) / 1e9
     step_gbps = (kv_bytes + qo_bytes) / K / (ms_per_step * 1e-3) / 1e9
@@ -169,7 +189,7 @@ def main():
         "metric": METRIC.get(args.workload, "decode attention tokens/s (all layers, %s)" % wl.name),
         "value": wl.B / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.dtype, "data": "synthetic",
+        "dtype": wl.dtype, "data": "synthetic", "launch": "hip-graph replay" if args.graph else "eager",
         "config": {"workload": "%s: L=%d w=%d Hq=%d Hkv=%d D=%d B=%d T=%s%s" % (
             wl.name, wl.L, wl.w, wl.Hq, wl.Hkv, wl.D, wl.B,
             wl.T if wl.T_min is None else "U[%d,%d]" % (wl.T_min, wl.T), " paged16" if wl.paged else ""),

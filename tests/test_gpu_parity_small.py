@@ -282,3 +282,37 @@ def test_call_errors_found_on_the_host_and_device_error_word():
         out = gc.step(q, kn, vn)
         assert gc.device_error() & lk.LCKV_DEV_ERR_BLOCK
         assert torch.isfinite(out[:, 0].float()).all()
+
+
+def test_step_captured_in_a_hip_graph_replays_like_eager_steps():
+    # lckv_step neither allocates nor synchronises, so a caller may capture it once (with a loose length bound)
+    # and replay it for successive tokens: lengths advance on the device inside the graph.  Every replay is
+    # checked against an eager step on a twin cache, with the program's own eager work between the replays.
+    wl = synth.Workload("t-graph", "bf16", L=4, w=2, Hq=8, Hkv=2, D=64, B=3, T=150, sigma=1.0, seed=26)
+    lens = np.array([150, 40, 97], np.int32)
+    K, V = synth.logical_cache(wl, 3, 150)
+    with GpuCache(wl, 176, lens, split_tokens=64) as eager, GpuCache(wl, 176, lens, split_tokens=64) as graphed:
+        for gc in (eager, graphed):
+            for s in range(3):
+                gc.load_dense(s, K[s], V[s])
+        q0, kn0, vn0 = synth.step_inputs(wl, 3)
+        sq, sk, sv = q0.cuda(), kn0.cuda(), vn0.cuda()           # static buffers the graph reads
+        sout = torch.zeros_like(sq)
+        ws = graphed.workspace(170)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            lk.lckv_step(graphed.h, sq, sk, sv, sout, graphed.lens, wl.B, 170, ws)
+        # capturing does not execute: lengths must be unchanged
+        assert (graphed.lens.cpu().numpy() == lens).all()
+        for step in range(5):
+            q, kn, vn = synth.step_inputs(wl, 3, step=step)
+            sq.copy_(q)
+            sk.copy_(kn)
+            sv.copy_(vn)
+            g.replay()
+            want = eager.step(q, kn, vn)                           # eager work and a sync between replays
+            torch.cuda.synchronize()
+            assert torch.equal(sout.cpu(), want.cpu()), "replay %d differs from the eager step" % step
+            assert (graphed.lens.cpu().numpy() == lens + step + 1).all()
+        assert graphed.device_error() == 0 and eager.device_error() == 0
