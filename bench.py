@@ -72,6 +72,54 @@ def cpu_baseline(sess, units, kv, q, k_new, v_new, out, target_cpu_s=12.0):
     }
 
 
+def residency_sweep(steps, warmup):
+    """Does the shared slot, re-read by each successive condensed layer, stay in the 256 MB last-level cache?
+    TinyLlama shape (C2) with the batch varied so that the shared slot goes from 32 MiB to 1 GiB; for plain and
+    nontemporal loads, the effective bandwidth (algorithmic bytes / kernel time, HIP events per launch) of the
+    condensed layers' launches (slot just read by the previous layer) and of the warmup layers' launches (slot
+    last read one step ago).  Prints one JSON line."""
+    import numpy as np
+    import torch
+    from paper_2405_10637_amd import binding as lk
+    from paper_2405_10637_amd import synth
+    from paper_2405_10637_amd.runner import DecodeSession
+
+    rows = []
+    for B in (16, 32, 48, 64, 96, 128, 192, 256, 512):
+        wl = synth.C2.with_(B=B, name="C2-shape-B%d" % B)
+        with DecodeSession(wl, room=2 * (steps + warmup) + 2) as sess:
+            sess.fill(())
+            q, k_new, v_new = synth.step_inputs(wl, sess.n_slots, device="cuda")
+            out = torch.empty_like(q)
+            per_key = 2 * wl.Hkv * wl.D * wl.elem_bytes
+            qo = 2 * wl.B * wl.Hq * wl.D * wl.elem_bytes
+            row = {"B": B, "shared_slot_MiB": B * wl.T * per_key / 2 ** 20}
+            for name, policy in (("plain", lk.LCKV_LOAD_TEMPORAL), ("nontemporal", lk.LCKV_LOAD_NONTEMPORAL)):
+                lk.lckv_set_load_policy(sess.h, policy)
+                for _ in range(warmup):
+                    sess.step(q, k_new, v_new, out)
+                torch.cuda.synchronize()
+                lk.lckv_profile_read(sess.h)
+                lk.lckv_profile_enable(sess.h, True)
+                first = sess.max_len - int(sess.lens0.max())
+                for _ in range(steps):
+                    sess.step(q, k_new, v_new, out)
+                ms = lk.lckv_profile_launch_ms(sess.h).reshape(steps, wl.L)
+                lk.lckv_profile_read(sess.h)
+                lk.lckv_profile_enable(sess.h, False)
+                vis = np.array([v for (_, v) in sess.kv_slot])
+                n_keys = wl.T + first + np.arange(steps)[:, None] + vis[None, :]
+                gbps = (wl.B * n_keys * per_key + qo) / (ms * 1e-3) / 1e9
+                row[name] = {"condensed_GBps": float(np.median(gbps[:, vis == 0][:, 1:])),   # skip the first: cold
+                             "first_condensed_GBps": float(np.median(gbps[:, vis == 0][:, 0])),
+                             "warmup_layer_GBps": float(np.median(gbps[:, vis == 1])),
+                             "condensed_launch_us": float(np.median(ms[:, vis == 0][:, 1:]) * 1e3)}
+            rows.append(row)
+    print(json.dumps({"metric": "shared-slot residency sweep, TinyLlama shape (L=22, 32/4 heads, D=64, T=2048)",
+                      "unit": "GB/s effective per attention launch", "hbm_peak_GBps": HBM_PEAK_GBPS,
+                      "last_level_cache_MiB": 256, "rows": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,9 +132,13 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="capture one lckv_step in a HIP graph (length bound = last timed step) and time replays")
+    ap.add_argument("--residency-sweep", action="store_true",
+                    help="instead of the benchmark: effective bandwidth vs size of the shared slot (C2 shape)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+    if args.residency_sweep:
+        return residency_sweep(args.steps, args.warmup)
 
     import numpy as np
     import torch

@@ -165,6 +165,10 @@ int lckv_last_device_error(lckv_cache *cache, int32_t *bits);
  * timed launches and their summed duration since the last read, and resets both. */
 int lckv_profile_enable(lckv_cache *cache, int32_t enable);
 int lckv_profile_read(lckv_cache *cache, int32_t *n_launches, double *total_ms);
+/* The individual durations (milliseconds, launch order) of the launches timed since the last lckv_profile_read:
+ * up to `capacity` of them are written to host array `ms`, *n_launches gets their number.  SYNCHRONISES; does not
+ * reset (call it before lckv_profile_read). */
+int lckv_profile_launch_ms(lckv_cache *cache, float *ms, int32_t capacity, int32_t *n_launches);
 
 /* Measurement aid: read `bytes` (a multiple of 2 MiB is read, the rest ignored) of device memory with the
  * attention kernel's load pattern (with or without the nontemporal hint) and discard them; timing it gives the

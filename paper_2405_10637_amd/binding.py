@@ -27,7 +27,8 @@ EXPORTS = [
     "lckv_cache_bytes", "lckv_cache_alloc", "lckv_cache_free", "lckv_cache_set_block_table", "lckv_n_slots",
     "lckv_kv_slot", "lckv_slot_producer", "lckv_append_kv", "lckv_decode_attention", "lckv_step",
     "lckv_workspace_bytes", "lckv_set_split_tokens", "lckv_set_load_policy", "lckv_cache_load_dense", "lckv_cache_read",
-    "lckv_last_device_error", "lckv_profile_enable", "lckv_profile_read", "lckv_hbm_read_probe", "lckv_strerror",
+    "lckv_last_device_error", "lckv_profile_enable", "lckv_profile_read", "lckv_profile_launch_ms",
+    "lckv_hbm_read_probe", "lckv_strerror",
 ]
 
 
@@ -79,6 +80,7 @@ def lib():
         L.lckv_profile_enable.argtypes = [vp, i32]
         L.lckv_profile_read.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double)]
         L.lckv_hbm_read_probe.argtypes = [vp, vp, sz, i32, vp]
+        L.lckv_profile_launch_ms.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
         L.lckv_strerror.argtypes = [ctypes.c_int]
         L.lckv_strerror.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -230,3 +232,10 @@ def lckv_profile_read(cache: int):
     n, ms = ctypes.c_int32(0), ctypes.c_double(0.0)
     _check(lib().lckv_profile_read(cache, ctypes.byref(n), ctypes.byref(ms)), "lckv_profile_read")
     return n.value, ms.value
+
+
+def lckv_profile_launch_ms(cache: int, capacity: int = 8192) -> np.ndarray:
+    ms = np.zeros(capacity, np.float32)
+    n = ctypes.c_int32(0)
+    _check(lib().lckv_profile_launch_ms(cache, ms.ctypes.data, capacity, ctypes.byref(n)), "lckv_profile_launch_ms")
+    return ms[: n.value].copy()

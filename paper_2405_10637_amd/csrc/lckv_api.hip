@@ -426,6 +426,17 @@ int lckv_profile_enable(lckv_cache *c, int32_t enable) {
     return LCKV_OK;
 }
 
+int lckv_profile_launch_ms(lckv_cache *c, float *ms, int32_t capacity, int32_t *n_launches) {
+    if (!valid(c) || !ms || !n_launches) return LCKV_ERR_NULL;
+    if (capacity < 0) return LCKV_ERR_RANGE;
+    if (hipDeviceSynchronize() != hipSuccess) return LCKV_ERR_HIP;
+    int32_t n = 0;
+    for (size_t i = 0; i + 1 < c->ev_used && n < capacity; i += 2, ++n)
+        if (hipEventElapsedTime(&ms[n], c->ev[i], c->ev[i + 1]) != hipSuccess) return LCKV_ERR_HIP;
+    *n_launches = n;
+    return LCKV_OK;
+}
+
 int lckv_profile_read(lckv_cache *c, int32_t *n_launches, double *total_ms) {
     if (!valid(c) || !n_launches || !total_ms) return LCKV_ERR_NULL;
     if (hipDeviceSynchronize() != hipSuccess) return LCKV_ERR_HIP;

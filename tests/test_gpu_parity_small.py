@@ -316,3 +316,56 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps():
             assert torch.equal(sout.cpu(), want.cpu()), "replay %d differs from the eager step" % step
             assert (graphed.lens.cpu().numpy() == lens + step + 1).all()
         assert graphed.device_error() == 0 and eager.device_error() == 0
+
+
+def test_per_layer_entry_points_compose_to_the_step():
+    # lckv_append_kv + lckv_decode_attention called layer by layer (producers appended first, lengths bumped by
+    # the caller) must give exactly what lckv_step gives, and must match the oracle.
+    for paged in (False, True):
+        wl = synth.Workload("t-layered", "bf16", L=5, w=2, Hq=8, Hkv=4, D=128, B=4, T=90, sigma=1.0, seed=27,
+                            paged=paged)
+        lens = np.array([90, 0, 31, 64], np.int32)
+        K, V = synth.logical_cache(wl, 3, 96)
+        q, kn, vn = synth.step_inputs(wl, 3)
+        with GpuCache(wl, 96, lens, split_tokens=32) as a, GpuCache(wl, 96, lens, split_tokens=32) as b:
+            for gc in (a, b):
+                for s in range(3):
+                    gc.load_dense(s, K[s, :, :90], V[s, :, :90])
+            want_step = a.step(q, kn, vn)
+            qd, knd, vnd = q.cuda(), kn.cuda(), vn.cuda()
+            out = torch.full_like(qd, float("nan"))
+            ws = b.workspace(91)
+            for l in range(wl.L):
+                for s in range(b.n_slots):
+                    if lk.lckv_slot_producer(b.h, s) == l:
+                        lk.lckv_append_kv(b.h, l, knd[s], vnd[s], b.lens, wl.B)
+                lk.lckv_decode_attention(b.h, l, qd[l], out[l], b.lens, wl.warmup_mask, wl.B, 90, ws)
+            torch.cuda.synchronize()
+            assert torch.equal(out.cpu(), want_step.cpu())
+            assert (b.lens.cpu().numpy() == lens).all()          # only lckv_step bumps the lengths
+            want, _ = orc.step(wl.warmup_mask, to_f32_numpy(K), to_f32_numpy(V), lens.copy(), to_f32_numpy(q),
+                               to_f32_numpy(kn), to_f32_numpy(vn), 1.0 / np.sqrt(wl.D))
+            check_close(out, want, "bf16", "per-layer calls")
+            assert a.device_error() == 0 and b.device_error() == 0
+
+
+def test_batch_smaller_than_capacity_and_group_of_16():
+    # B < B_max, and G = 16 query heads per kv head (all 16 columns of the matrix tile in use)
+    wl_cap = synth.Workload("t-cap", "bf16", L=3, w=1, Hq=32, Hkv=2, D=64, B=6, T=70, sigma=1.0, seed=28)
+    wl = wl_cap.with_(B=3)
+    lens = np.array([70, 17, 48, 0, 0, 0], np.int32)
+    K, V = synth.logical_cache(wl_cap, 2, 80)
+    with GpuCache(wl_cap, 80, lens, split_tokens=32) as gc:
+        for s in range(2):
+            gc.load_dense(s, K[s, :, :70], V[s, :, :70])
+        q, kn, vn = synth.step_inputs(wl, 2)
+        qd, knd, vnd = q.cuda(), kn.cuda(), vn.cuda()
+        out = torch.full_like(qd, float("nan"))
+        lk.lckv_step(gc.h, qd, knd, vnd, out, gc.lens, 3, 70, gc.workspace(71))
+        torch.cuda.synchronize()
+        lens3 = lens[:3].copy()
+        want, _ = orc.step(wl.warmup_mask, to_f32_numpy(K[:, :3]), to_f32_numpy(V[:, :3]), lens3, to_f32_numpy(q),
+                           to_f32_numpy(kn), to_f32_numpy(vn), 1.0 / np.sqrt(wl.D))
+        check_close(out, want, "bf16", "B < B_max, G = 16")
+        assert gc.lens.cpu().numpy().tolist() == [71, 18, 49, 0, 0, 0]       # the other sequences are untouched
+        assert gc.device_error() == 0
