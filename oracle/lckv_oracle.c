@@ -18,6 +18,9 @@
  * attention when every layer is a warmup layer (Section 4.2, caption of the
  * warmup-layer figure: w = L is exactly the standard transformer), a library
  * softmax/matmul evaluation, invariants.
+ * The sink + window cache policy of Section 3.3 (StreamingLLM integration) is
+ * an option of the step; it is written as a selection of logical positions
+ * from the full history, not as a ring buffer.
  * "Parity unpinned": which layer owns the shared cache when the topmost
  * layers are warmup layers (pairing rule 1 vs rule 2 below) is not decided by
  * the paper; both are implemented, rule 1 is the default.
@@ -179,13 +182,23 @@ int lckv_oracle_attend_many(int64_t n_items, const float *q, const float *K,
  *   out      [L][B][Hq][D] double
  * Returns the thread count used (>0), or a negative value on error
  * (-1 bad argument, -2 a sequence is already at capacity).
+ *
+ * Sink + window policy (Section 3.3, integration with StreamingLLM: only the
+ * K/V of the first few tokens - four by default - and of the recent tokens are
+ * kept): with window > 0, of a query's n candidate positions 0..n-1 only the
+ * first `sink` and the last `window` are attended to.  The oracle keeps the
+ * whole history in Kc, Vc and selects those positions by their logical index;
+ * window = 0 switches the policy off.
  */
-int lckv_oracle_step(int L, int Hq, int Hkv, int D, int B, int64_t T_cap,
-                     const uint8_t *warm, int rule, double scale, float *Kc,
-                     float *Vc, int32_t *lens, const float *q,
-                     const float *k_new, const float *v_new, double *out,
-                     int threads)
+int lckv_oracle_step_streaming(int L, int Hq, int Hkv, int D, int B,
+                               int64_t T_cap, const uint8_t *warm, int rule,
+                               double scale, float *Kc, float *Vc,
+                               int32_t *lens, const float *q,
+                               const float *k_new, const float *v_new,
+                               double *out, int64_t sink, int64_t window,
+                               int threads)
 {
+    if (sink < 0 || window < 0) return -1;
     if (L <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || B <= 0 || T_cap <= 0 ||
         Hq % Hkv != 0)
         return -1;
@@ -231,6 +244,20 @@ int lckv_oracle_step(int L, int Hq, int Hkv, int D, int B, int64_t T_cap,
             int64_t n = (int64_t)lens[b] + (self_visible[l] ? 1 : 0);
             int64_t base = s * slot_sz + b * seq + (int64_t)g * D;
             int64_t qo = (((int64_t)l * B + b) * Hq + h) * D;
+            if (window > 0 && n > sink + window) {
+                /* kept set: positions [0, sink) and [n - window, n) */
+                int64_t kept = sink + window;
+                float *Kk = (float *)malloc(sizeof(float) * (size_t)(kept * D) * 2);
+                float *Vk = Kk + kept * D;
+                for (int64_t i = 0; i < kept; ++i) {
+                    int64_t j = i < sink ? i : n - window + (i - sink);
+                    memcpy(Kk + i * D, Kc + base + j * row, sizeof(float) * (size_t)D);
+                    memcpy(Vk + i * D, Vc + base + j * row, sizeof(float) * (size_t)D);
+                }
+                lckv_oracle_attend(q + qo, Kk, Vk, kept, D, D, scale, out + qo, NULL);
+                free(Kk);
+                continue;
+            }
             lckv_oracle_attend(q + qo, Kc + base, Vc + base, n, row, D, scale,
                                out + qo, NULL);
         }
@@ -238,6 +265,18 @@ int lckv_oracle_step(int L, int Hq, int Hkv, int D, int B, int64_t T_cap,
     for (int b = 0; b < B; ++b) lens[b] += 1;
     free(kv_slot);
     return used;
+}
+
+/* The step without the sink + window policy: every cached position is kept. */
+int lckv_oracle_step(int L, int Hq, int Hkv, int D, int B, int64_t T_cap,
+                     const uint8_t *warm, int rule, double scale, float *Kc,
+                     float *Vc, int32_t *lens, const float *q,
+                     const float *k_new, const float *v_new, double *out,
+                     int threads)
+{
+    return lckv_oracle_step_streaming(L, Hq, Hkv, D, B, T_cap, warm, rule,
+                                      scale, Kc, Vc, lens, q, k_new, v_new,
+                                      out, 0, 0, threads);
 }
 
 int lckv_oracle_max_threads(void)

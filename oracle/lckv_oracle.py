@@ -67,6 +67,10 @@ def _load():
                                                               ctypes.c_double, f32p, f32p, i32p, f32p, f32p,
                                                               f32p, f64p, ctypes.c_int]
         lib.lckv_oracle_step.restype = ctypes.c_int
+        lib.lckv_oracle_step_streaming.argtypes = [ctypes.c_int] * 5 + [
+            ctypes.c_int64, u8p, ctypes.c_int, ctypes.c_double, f32p, f32p, i32p, f32p, f32p, f32p, f64p,
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
+        lib.lckv_oracle_step_streaming.restype = ctypes.c_int
         lib.lckv_oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -138,12 +142,14 @@ def attend_many(q, K, V, n_keys, scale: float, threads: int = 0):
 
 
 def step(warm, Kc, Vc, lens, q, k_new, v_new, scale: float, rule: int = PAIR_TOP_OF_CONDENSED,
-         threads: int = 0):
+         threads: int = 0, sink: int = 0, window: int = 0):
     """One decode step.
 
     Kc, Vc: float32 [n_slots][B][T_cap][Hkv][D], C-contiguous, UPDATED IN PLACE (the new token is
     appended); lens: int32 [B], UPDATED IN PLACE (+1); q: [L][B][Hq][D]; k_new, v_new:
     [n_slots][B][Hkv][D] in slot order.  Returns (out float64 [L][B][Hq][D], threads used).
+    window > 0: sink + window policy (Section 3.3): only the first `sink` and the last `window` of a query's
+    candidate positions are attended to; Kc, Vc still hold the whole history.
     """
     warm = np.ascontiguousarray(np.asarray(warm, dtype=np.uint8))
     L = warm.shape[0]
@@ -160,10 +166,13 @@ def step(warm, Kc, Vc, lens, q, k_new, v_new, scale: float, rule: int = PAIR_TOP
     _, _, prod = pairing(warm, rule)
     assert len(prod) == n_slots, "cache has %d slots, pairing needs %d" % (n_slots, len(prod))
     out = np.zeros((L, B, Hq, D), np.float64)
-    rc = _load().lckv_oracle_step(L, Hq, Hkv, D, B, T_cap, _p(warm, ctypes.c_uint8), rule, float(scale),
-                                  _p(Kc, ctypes.c_float), _p(Vc, ctypes.c_float), _p(lens, ctypes.c_int32),
-                                  _p(q, ctypes.c_float), _p(k_new, ctypes.c_float), _p(v_new, ctypes.c_float),
-                                  _p(out, ctypes.c_double), threads)
+    args = (L, Hq, Hkv, D, B, T_cap, _p(warm, ctypes.c_uint8), rule, float(scale),
+            _p(Kc, ctypes.c_float), _p(Vc, ctypes.c_float), _p(lens, ctypes.c_int32),
+            _p(q, ctypes.c_float), _p(k_new, ctypes.c_float), _p(v_new, ctypes.c_float), _p(out, ctypes.c_double))
+    if window > 0 or sink > 0:
+        rc = _load().lckv_oracle_step_streaming(*args, int(sink), int(window), threads)
+    else:
+        rc = _load().lckv_oracle_step(*args, threads)
     if rc < 0:
         raise ValueError("lckv_oracle_step failed with code %d" % rc)
     return out, int(rc)

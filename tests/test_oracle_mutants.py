@@ -30,6 +30,10 @@ MUTANTS = {
     "warmup reads shared slot": ("kv_slot[l] = slot_of_layer[l];",
                                  "kv_slot[l] = slot_of_layer[shared_producer < 0 ? l : shared_producer];"),
     "kv head stride wrong": ("b * seq + (int64_t)g * D;", "b * seq + (int64_t)g;"),
+    "window starts one early": ("i < sink ? i : n - window + (i - sink);", "i < sink ? i : n - window - 1 + (i - sink);"),
+    "sinks not kept": ("int64_t j = i < sink ? i :", "int64_t j = i < sink ? sink + i :"),
+    "sink window policy ignored": ("if (window > 0 && n > sink + window) {", "if (0 && n > sink + window) {"),
+    "kept values taken from K": ("memcpy(Vk + i * D, Vc + base", "memcpy(Vk + i * D, Kc + base"),
 }
 
 PIN_FUNCS = [getattr(pins, n) for n in dir(pins) if n.startswith("test_")]

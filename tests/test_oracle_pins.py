@@ -392,3 +392,97 @@ def test_step_rejects_a_full_sequence():
     K, V, lens, q, kn, vn = make_state(1, 1, 1, 1, 4, 4, warm, 0, 160, lens=[4])
     with pytest.raises(ValueError):
         orc.step(warm, K, V, lens, q, kn, vn, 1.0)
+
+
+# ---------------------------------------------------------------- sink + window policy (Section 3.3)
+
+def kept_positions(n, sink, window):
+    """Written out by hand for the tests: first `sink` and last `window` of positions 0..n-1."""
+    if window <= 0 or n <= sink + window:
+        return list(range(n))
+    return list(range(sink)) + list(range(n - window, n))
+
+
+def test_streaming_kept_sets_by_hand():
+    # StreamingLLM keeps the K/V of the first few tokens and of the recent tokens (Section 3.3).
+    assert kept_positions(10, 2, 3) == [0, 1, 7, 8, 9]
+    assert kept_positions(11, 2, 3) == [0, 1, 8, 9, 10]
+    assert kept_positions(5, 2, 3) == [0, 1, 2, 3, 4]
+    assert kept_positions(6, 4, 1) == [0, 1, 2, 3, 5]
+
+
+def test_streaming_zero_query_gives_the_mean_over_the_kept_set():
+    warm = [1, 0, 0]
+    L, B, Hq, Hkv, D, T_cap = 3, 1, 2, 2, 4, 16
+    K, V, lens, q, kn, vn = make_state(L, B, Hq, Hkv, D, T_cap, warm, 0, 200, lens=[10])
+    q[:] = 0
+    V0 = V.copy()
+    out, _ = orc.step(warm, K, V, lens, q, kn, vn, 1.0, sink=2, window=3)
+    # condensed layers: 10 candidates -> {0,1,7,8,9}; warmup layer: 11 candidates -> {0,1,8,9,new}
+    want_cond = V0[1, 0, [0, 1, 7, 8, 9]].astype(np.float64).mean(0)
+    want_warm = (V0[0, 0, [0, 1, 8, 9]].astype(np.float64).sum(0) + vn[0, 0]) / 5.0
+    np.testing.assert_allclose(out[1, 0], want_cond, atol=1e-14)
+    np.testing.assert_allclose(out[2, 0], want_cond, atol=1e-14)
+    np.testing.assert_allclose(out[0, 0], want_warm, atol=1e-14)
+
+
+def test_streaming_with_a_wide_window_equals_the_full_cache_bitwise():
+    warm = [1, 0, 0, 1]
+    L, B, Hq, Hkv, D, T_cap = 4, 3, 4, 2, 8, 20
+    base = make_state(L, B, Hq, Hkv, D, T_cap, warm, 0, 210, lens=[0, 7, 15])
+    a = [x.copy() for x in base]
+    b = [x.copy() for x in base]
+    oa, _ = orc.step(warm, *a, 0.3)
+    ob, _ = orc.step(warm, *b, 0.3, sink=4, window=12)          # 4 + 12 >= 16 candidates: nothing dropped
+    np.testing.assert_array_equal(oa, ob)
+
+
+def test_streaming_matches_library_evaluation_on_the_hand_built_kept_set():
+    warm = [0, 1, 0]
+    L, B, Hq, Hkv, D, T_cap = 3, 2, 4, 2, 8, 40
+    sink, window = 4, 6
+    K, V, lens, q, kn, vn = make_state(L, B, Hq, Hkv, D, T_cap, warm, 0, 220, lens=[30, 9])
+    K0, V0, lens0 = K.copy(), V.copy(), lens.copy()
+    out, _ = orc.step(warm, K, V, lens, q, kn, vn, 0.4, sink=sink, window=window)
+    slot, vis, prod = [1, 0, 1], [0, 1, 0], [1, 2]              # by hand: layer 1 warm, top condensed layer 2
+    for l in range(L):
+        s = slot[l]
+        for b in range(B):
+            t = int(lens0[b])
+            Ks, Vs = K0[s, b, :t].astype(np.float64), V0[s, b, :t].astype(np.float64)
+            if vis[l]:
+                Ks = np.concatenate([Ks, kn[s, b][None]], 0)
+                Vs = np.concatenate([Vs, vn[s, b][None]], 0)
+            keep = kept_positions(Ks.shape[0], sink, window)
+            for h in range(Hq):
+                g = h // 2
+                p = scipy.special.softmax(0.4 * (Ks[keep, g] @ q[l, b, h].astype(np.float64)))
+                np.testing.assert_allclose(out[l, b, h], p @ Vs[keep, g], rtol=0, atol=1e-13)
+
+
+def test_streaming_needles_evicted_sink_and_window_edges():
+    warm = [0]
+    L, B, Hq, Hkv, D, T_cap = 1, 1, 1, 1, 16, 64
+    sink, window, t = 4, 8, 40                   # kept: 0..3 and 32..39
+    for pos, visible in [(0, True), (3, True), (4, False), (20, False), (31, False), (32, True), (39, True)]:
+        K, V, lens, q, kn, vn = make_state(L, B, Hq, Hkv, D, T_cap, warm, 0, 230, lens=[t])
+        K[0, 0, pos, 0] = 60.0 * q[0, 0, 0] / np.linalg.norm(q[0, 0, 0])
+        target = V[0, 0, pos, 0].astype(np.float64)
+        out, _ = orc.step(warm, K, V, lens, q, kn, vn, 1.0, sink=sink, window=window)
+        if visible:
+            np.testing.assert_allclose(out[0, 0, 0], target, atol=1e-9)
+        else:
+            assert np.abs(out[0, 0, 0] - target).max() > 1e-2
+
+
+def test_streaming_window_slides_one_position_per_step():
+    warm = [0, 0]
+    L, B, Hq, Hkv, D, T_cap = 2, 1, 1, 1, 4, 32
+    K, V, lens, q, kn, vn = make_state(L, B, Hq, Hkv, D, T_cap, warm, 0, 240, lens=[12])
+    q[:] = 0
+    for step in range(4):
+        t = 12 + step
+        V_before = V.copy()
+        out, _ = orc.step(warm, K, V, lens, q, kn, vn, 1.0, sink=1, window=5)
+        keep = [0] + list(range(t - 5, t))
+        np.testing.assert_allclose(out[0, 0, 0], V_before[0, 0, keep, 0].astype(np.float64).mean(0), atol=1e-14)
