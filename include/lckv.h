@@ -80,6 +80,15 @@ typedef struct lckv_config {
     const uint8_t *warmup_mask; /* host, L bytes, 1 = warmup layer (Section 2.1); copied */
     int32_t pairing_rule; /* LCKV_PAIR_* */
     float scale;          /* softmax scale; 0 means 1/sqrt(D) (the paper does not state it) */
+    /* Sink + window policy (Section 3.3, integration with StreamingLLM: only the K/V of the first few tokens and
+     * of the recent tokens are kept).  window_tokens = 0: off.  Otherwise every slot keeps the first sink_tokens
+     * positions and a ring of the last window_tokens positions (position t >= sink lives in entry
+     * sink + (t - sink) % window), sequences may grow without bound, a condensed layer attends to the sinks and
+     * the last `window` previous tokens, a warmup layer to the sinks and the last `window` tokens including the
+     * one being decoded.  Needs sink_tokens + window_tokens <= the layout's capacity (T_max, or 16 * blocks per
+     * sequence).  RoPE re-indexing inside the window is outside this library: K arrives position-encoded. */
+    int32_t sink_tokens;
+    int32_t window_tokens;
 } lckv_config;
 
 /* Bytes of device storage a cache with this config needs (all slots).  Host only. */
@@ -107,7 +116,10 @@ int lckv_slot_producer(const lckv_cache *cache, int32_t slot, int32_t *layer);
 /* Store the new token's K/V of a producing layer: for every b < B,
  *   K[slot(layer)][b][t_b] = k_new[b], V[...] = v_new[b]      (bits copied unchanged)
  * k_new, v_new: device [B][Hkv][D].  dev_seq_lens: device int32[B], read, not changed.
- * A sequence already at capacity is skipped and LCKV_DEV_ERR_CAPACITY is raised on the device. */
+ * A sequence already at capacity is skipped and LCKV_DEV_ERR_CAPACITY is raised on the device (never with the
+ * sink + window policy, where the entry of the oldest recent token is overwritten).  With that policy the new
+ * K/V of the shared slot must be appended AFTER the condensed layers of the step have attended (lckv_step does
+ * so): before, it would overwrite a token they still see.  Warmup layers append before their own attention. */
 int lckv_append_kv(lckv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
                    const int32_t *dev_seq_lens, int32_t B, void *hip_stream);
 
@@ -124,8 +136,10 @@ int lckv_decode_attention(lckv_cache *cache, int32_t layer, const void *q, void 
                           int32_t max_len_hint, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* The whole step: layers in index order (layer l+1 starts after layer l has finished: in the model its query
- * depends on layer l's output); a producing layer's K/V are appended just before its attention; at the end
- * every t_b is incremented on the device.
+ * depends on layer l's output); a warmup layer's K/V are appended just before its attention (it sees itself),
+ * the shared slot's new K/V just after the attention of the condensed layer that produces them (the diagonal is
+ * masked, so no condensed layer sees them in this step); at the end every t_b is incremented on the device.
+ * With the sink + window policy max_len_hint may exceed the capacity.
  *   q_all, out_all: device [L][B][Hq][D];  k_new_all, v_new_all: device [n_slots][B][Hkv][D], slot order. */
 int lckv_step(lckv_cache *cache, const void *q_all, const void *k_new_all, const void *v_new_all, void *out_all,
               int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint, void *workspace, size_t workspace_bytes,

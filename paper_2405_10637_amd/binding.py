@@ -38,7 +38,7 @@ class lckv_config(ctypes.Structure):
         ("dtype", ctypes.c_int32), ("B_max", ctypes.c_int32), ("T_max", ctypes.c_int32),
         ("page_size", ctypes.c_int32), ("num_blocks", ctypes.c_int64),
         ("warmup_mask", ctypes.POINTER(ctypes.c_uint8)), ("pairing_rule", ctypes.c_int32),
-        ("scale", ctypes.c_float),
+        ("scale", ctypes.c_float), ("sink_tokens", ctypes.c_int32), ("window_tokens", ctypes.c_int32),
     ]
 
 
@@ -116,10 +116,11 @@ def _stream(stream) -> Optional[int]:
 
 
 def make_config(L, Hq, Hkv, D, dtype, B_max, T_max, warmup_mask, page_size=0, num_blocks=0,
-                pairing_rule=LCKV_PAIR_TOP_OF_CONDENSED, scale=0.0) -> lckv_config:
+                pairing_rule=LCKV_PAIR_TOP_OF_CONDENSED, scale=0.0, sink_tokens=0, window_tokens=0) -> lckv_config:
     mask = np.ascontiguousarray(np.asarray(warmup_mask, dtype=np.uint8))
     cfg = lckv_config(L, Hq, Hkv, D, dtype, B_max, T_max, page_size, num_blocks,
-                      mask.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), pairing_rule, scale)
+                      mask.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), pairing_rule, scale, sink_tokens,
+                      window_tokens)
     cfg._mask_keepalive = mask
     return cfg
 

@@ -172,7 +172,7 @@ __global__ __launch_bounds__(W * 64) void attn_bf16_kernel(AttnParams p) {
     int n = p.seq_lens[b] + p.self_visible;
     if (n > p.max_n) {
         n = p.max_n;
-        if (tid == 0) atomicOr(p.dev_err, LCKV_DEV_ERR_CAPACITY);
+        if (tid == 0 && !p.clamp_is_policy) atomicOr(p.dev_err, LCKV_DEV_ERR_CAPACITY);
     }
     if (n < 0) n = 0;
     const int k_begin = split * p.split_tokens;

@@ -36,6 +36,7 @@ __global__ void append_kernel(SlotView sv, const E *k_new, const E *v_new, const
     int g = (int)((i / D) % sv.Hkv);
     int b = (int)(i / ((int64_t)D * sv.Hkv));
     int t = seq_lens[b];
+    if (t >= 0) t = entry_of_position(sv, t);  // identity, or the ring entry under the sink + window policy
     if (t < 0 || t >= sv.capacity) {
         if (d == 0) atomicOr(dev_err, LCKV_DEV_ERR_CAPACITY);
         return;
@@ -92,7 +93,7 @@ __global__ void gather_kernel(SlotView sv, int b, int pos, int n_pos, int D, E *
     if (i >= total) return;
     int d = (int)(i % D);
     int g = (int)((i / D) % sv.Hkv);
-    int t = pos + (int)(i / ((int64_t)D * sv.Hkv));
+    int t = entry_of_position(sv, pos + (int)(i / ((int64_t)D * sv.Hkv)));
     int64_t idx = page_pair_index(sv, b, g, t / kPage);
     if (idx < 0) {
         if (d == 0) atomicOr(dev_err, LCKV_DEV_ERR_BLOCK);

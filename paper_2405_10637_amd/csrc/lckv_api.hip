@@ -38,6 +38,12 @@ int check_config(const lckv_config *cfg) {
     if (cfg->pairing_rule != LCKV_PAIR_TOP_OF_CONDENSED && cfg->pairing_rule != LCKV_PAIR_LAST_LAYER)
         return LCKV_ERR_CONFIG;
     if (!(cfg->scale >= 0.f) || isinf(cfg->scale)) return LCKV_ERR_CONFIG;
+    if (cfg->sink_tokens < 0 || cfg->window_tokens < 0) return LCKV_ERR_CONFIG;
+    if (cfg->window_tokens == 0 && cfg->sink_tokens != 0) return LCKV_ERR_CONFIG;
+    if ((int64_t)cfg->sink_tokens + cfg->window_tokens > (1 << 24)) return LCKV_ERR_CONFIG;
+    if (cfg->page_size == 0 && cfg->window_tokens > 0 &&
+        cfg->sink_tokens + cfg->window_tokens > (cfg->T_max + kPage - 1) / kPage * kPage)
+        return LCKV_ERR_CONFIG;
     for (int l = 0; l < cfg->L; ++l)
         if (cfg->warmup_mask[l] > 1) return LCKV_ERR_CONFIG;
     return LCKV_OK;
@@ -88,6 +94,18 @@ Geometry geometry(const lckv_config &cfg) {
     return g;
 }
 
+// Positions a sequence can hold at once: the layout's capacity, or sink + window under that policy.
+int kept_capacity(const lckv_cache *c) {
+    return c->cfg.window_tokens > 0 ? c->cfg.sink_tokens + c->cfg.window_tokens : c->capacity;
+}
+
+// Upper bound on the keys a query with `hint` cached tokens (+ itself if `self`) attends to.
+int visible_bound(const lckv_cache *c, int hint, int self) {
+    int64_t n = (int64_t)hint + self;
+    if (c->cfg.window_tokens > 0 && n > kept_capacity(c)) n = kept_capacity(c);
+    return (int)n;
+}
+
 SlotView slot_view(const lckv_cache *c, int slot) {
     SlotView v;
     v.base = c->storage + (size_t)slot * c->slot_bytes;
@@ -97,7 +115,9 @@ SlotView slot_view(const lckv_cache *c, int slot) {
     v.pages_per_seq = c->pages_per_seq;
     v.Hkv = c->cfg.Hkv;
     v.page_bytes = c->page_bytes;
-    v.capacity = c->capacity;
+    v.capacity = kept_capacity(c);
+    v.ring_sink = c->cfg.sink_tokens;
+    v.ring_window = c->cfg.window_tokens;
     return v;
 }
 
@@ -140,7 +160,7 @@ int attention_impl(lckv_cache *c, int layer, const void *q, void *out, const int
                    void *workspace, size_t workspace_bytes, hipStream_t stream) {
     const lckv_config &cfg = c->cfg;
     const int self = c->self_visible[layer];
-    const int max_n = max_len_hint + self;
+    const int max_n = visible_bound(c, max_len_hint, self);
     SplitPlan sp = plan_splits(c, B, max_n);
     size_t need = workspace_need(c, B, sp.n_splits);
     if (need > 0) {
@@ -161,6 +181,7 @@ int attention_impl(lckv_cache *c, int layer, const void *q, void *out, const int
     p.G = cfg.Hq / cfg.Hkv;
     p.self_visible = self;
     p.max_n = max_n;
+    p.clamp_is_policy = cfg.window_tokens > 0 && max_n == kept_capacity(c);
     p.split_tokens = sp.tokens;
     p.n_splits = sp.n_splits;
     p.scale_log2e = c->scale * 1.4426950408889634f;
@@ -185,7 +206,9 @@ int attention_impl(lckv_cache *c, int layer, const void *q, void *out, const int
 int check_call(const lckv_cache *c, int B, int max_len_hint, int extra) {
     if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
     if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
-    if (max_len_hint < 0 || (int64_t)max_len_hint + extra > c->capacity) return LCKV_ERR_LENGTH;
+    if (max_len_hint < 0) return LCKV_ERR_LENGTH;
+    if (c->cfg.window_tokens == 0 && (int64_t)max_len_hint + extra > c->capacity) return LCKV_ERR_LENGTH;
+    if (c->cfg.window_tokens > 0 && kept_capacity(c) > c->capacity) return LCKV_ERR_BLOCK_TABLE;
     return LCKV_OK;
 }
 
@@ -332,7 +355,7 @@ int lckv_step(lckv_cache *c, const void *q_all, const void *k_new_all, const voi
     const size_t q_layer = (size_t)B * cfg.Hq * cfg.D * eb;
     const size_t kv_slot_sz = (size_t)B * cfg.Hkv * cfg.D * eb;
     hipStream_t stream = (hipStream_t)hip_stream;
-    for (int l = 0; l < cfg.L; ++l) {
+    auto append_slots_of = [&](int l) -> int {
         for (int s = 0; s < c->n_slots; ++s) {
             if (c->producer[s] != l) continue;
             hipError_t e = launch_append(slot_view(c, s), (const char *)k_new_all + s * kv_slot_sz,
@@ -340,9 +363,18 @@ int lckv_step(lckv_cache *c, const void *q_all, const void *k_new_all, const voi
                                          c->dev_err, stream);
             if (e != hipSuccess) return LCKV_ERR_HIP;
         }
+        return LCKV_OK;
+    };
+    for (int l = 0; l < cfg.L; ++l) {
+        // A warmup layer sees the token being decoded: its K/V go in first.  The shared slot's new K/V are
+        // invisible to every condensed layer of this step (diagonal mask) and, under the sink + window policy,
+        // replace an entry those layers still read: they go in after the producing layer's attention.
+        const bool before = c->self_visible[l] != 0;
+        if (before && (rc = append_slots_of(l)) != LCKV_OK) return rc;
         rc = attention_impl(c, l, (const char *)q_all + l * q_layer, (char *)out_all + l * q_layer, dev_seq_lens, B,
                             max_len_hint, workspace, workspace_bytes, stream);
         if (rc != LCKV_OK) return rc;
+        if (!before && (rc = append_slots_of(l)) != LCKV_OK) return rc;
     }
     return launch_bump(dev_seq_lens, B, stream) == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
 }
@@ -351,8 +383,8 @@ int lckv_workspace_bytes(const lckv_cache *c, int32_t B, int32_t max_len_hint, s
     if (!valid(c) || !bytes) return LCKV_ERR_NULL;
     if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
     if (max_len_hint < 0) return LCKV_ERR_LENGTH;
-    size_t a = workspace_need(c, B, plan_splits(c, B, max_len_hint).n_splits);
-    size_t b = workspace_need(c, B, plan_splits(c, B, max_len_hint + 1).n_splits);
+    size_t a = workspace_need(c, B, plan_splits(c, B, visible_bound(c, max_len_hint, 0)).n_splits);
+    size_t b = workspace_need(c, B, plan_splits(c, B, visible_bound(c, max_len_hint, 1)).n_splits);
     *bytes = a > b ? a : b;
     return LCKV_OK;
 }
@@ -378,7 +410,7 @@ int lckv_cache_load_dense(lckv_cache *c, int32_t slot, const void *k, const void
     if (slot < 0 || slot >= c->n_slots) return LCKV_ERR_LAYER;
     if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
     if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
-    if (T < 0 || T > c->capacity) return LCKV_ERR_LENGTH;
+    if (T < 0 || T > kept_capacity(c) || kept_capacity(c) > c->capacity) return LCKV_ERR_LENGTH;
     hipError_t e = launch_load_dense(slot_view(c, slot), k, v, dev_seq_lens, B, T, c->cfg.D, c->cfg.dtype,
                                      c->dev_err, (hipStream_t)hip_stream);
     return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
@@ -389,7 +421,10 @@ int lckv_cache_read(lckv_cache *c, int32_t slot, int32_t b, int32_t pos, int32_t
     if (slot < 0 || slot >= c->n_slots) return LCKV_ERR_LAYER;
     if (b < 0 || b >= c->cfg.B_max) return LCKV_ERR_BATCH;
     if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
-    if (pos < 0 || n_pos < 1 || (int64_t)pos + n_pos > c->capacity) return LCKV_ERR_RANGE;
+    // under the sink + window policy `pos` is a logical position of any size; the caller asks only for
+    // positions that are still kept
+    if (pos < 0 || n_pos < 1 || n_pos > kept_capacity(c) || kept_capacity(c) > c->capacity) return LCKV_ERR_RANGE;
+    if (c->cfg.window_tokens == 0 && (int64_t)pos + n_pos > c->capacity) return LCKV_ERR_RANGE;
     if ((int64_t)n_pos * c->cfg.Hkv * c->cfg.D >= ((int64_t)1 << 31)) return LCKV_ERR_RANGE;
     size_t bytes = (size_t)n_pos * c->cfg.Hkv * c->cfg.D * elem_bytes(c->cfg.dtype);
     char *tmp = nullptr;

@@ -22,8 +22,18 @@ struct SlotView {
     int32_t pages_per_seq;      // contiguous: pages per (b, kv head)
     int32_t Hkv;
     int32_t page_bytes;         // bytes of one K (or V) page = 16 * D * elem
-    int32_t capacity;           // positions a sequence can hold
+    int32_t capacity;           // positions a sequence can hold (sink + window with the sink + window policy)
+    int32_t ring_sink;          // sink + window policy: positions below this stay where they are
+    int32_t ring_window;        // ... and later positions live in a ring of this many entries; 0 = policy off
 };
+
+// Entry of a slot that holds logical position t: identity, or with the sink + window policy the ring entry
+// (Section 3.3 of the LCKV paper: the first few and the recent tokens are kept).
+__device__ __forceinline__ int entry_of_position(const SlotView &v, int t) {
+    if (v.ring_window > 0 && t >= v.ring_sink + v.ring_window)
+        return v.ring_sink + (t - v.ring_sink) % v.ring_window;
+    return t;
+}
 
 // Index of the page pair holding page p of (b, kv head g); -1 if the block table entry is invalid.
 __device__ __forceinline__ int64_t page_pair_index(const SlotView &v, int b, int g, int p) {
@@ -65,6 +75,7 @@ struct AttnParams {
     int32_t B, Hq, Hkv, G;
     int32_t self_visible;       // 1: n_b = t_b + 1
     int32_t max_n;              // clamp for n_b
+    int32_t clamp_is_policy;    // 1: n_b > max_n is the sink + window policy at work, not an error
     int32_t split_tokens;       // keys per split (multiple of 16)
     int32_t n_splits;
     float scale_log2e;          // scale * log2(e)

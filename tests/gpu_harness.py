@@ -32,19 +32,21 @@ class GpuCache:
     """A cache on the GPU for workload `wl`: storage poisoned with NaN bit patterns, optional block table."""
 
     def __init__(self, wl: synth.Workload, T_cap: int, lens: np.ndarray, rule=lk.LCKV_PAIR_TOP_OF_CONDENSED,
-                 split_tokens: int = 0, scale: float = 0.0, poison: bool = True, load_policy: int = 0):
+                 split_tokens: int = 0, scale: float = 0.0, poison: bool = True, load_policy: int = 0,
+                 sink: int = 0, window: int = 0):
         self.wl = wl
         self.lens0 = np.asarray(lens, np.int32).copy()
         self.table = None
         if wl.paged:
             table, num_blocks = synth.block_table(wl, np.full(wl.B, T_cap - 1, np.int32))
             self.cfg = lk.make_config(wl.L, wl.Hq, wl.Hkv, wl.D, lk_dtype(wl), wl.B, 0, wl.warmup_mask, page_size=16,
-                                      num_blocks=num_blocks, pairing_rule=rule, scale=scale)
+                                      num_blocks=num_blocks, pairing_rule=rule, scale=scale, sink_tokens=sink,
+                                      window_tokens=window)
             self.table = torch.from_numpy(table).to(DEV)
             self.capacity = table.shape[1] * 16
         else:
             self.cfg = lk.make_config(wl.L, wl.Hq, wl.Hkv, wl.D, lk_dtype(wl), wl.B, T_cap, wl.warmup_mask,
-                                      pairing_rule=rule, scale=scale)
+                                      pairing_rule=rule, scale=scale, sink_tokens=sink, window_tokens=window)
             self.capacity = (T_cap + 15) // 16 * 16
         nbytes = lk.lckv_cache_bytes(self.cfg)
         self.storage = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
