@@ -129,9 +129,15 @@ def main():
     ap.add_argument("--split-tokens", type=int, default=0)
     ap.add_argument("--load-policy", type=int, default=0, help="0 auto, 1 plain loads, 2 nontemporal loads")
     ap.add_argument("--sample", type=int, default=768, help="units the CPU oracle is timed and checked on")
+    ap.add_argument("--capacity", type=int, default=0,
+                    help="positions per sequence the cache is built for (default: just enough for this run); the "
+                         "distance between two sequences' streams in HBM follows from it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="capture one lckv_step in a HIP graph (length bound = last timed step) and time replays")
+    ap.add_argument("--chain", action="store_true",
+                    help="feed layer l's output into layer l+1's query (q[l+1] = q_seed[l+1] + out[l]) so the "
+                         "layer-to-layer dependency of the model is physically real; per-layer entry points")
     ap.add_argument("--residency-sweep", action="store_true",
                     help="instead of the benchmark: effective bandwidth vs size of the shared slot (C2 shape)")
     args = ap.parse_args()
@@ -152,7 +158,13 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     K, W = args.steps, args.warmup
 
-    sess = DecodeSession(wl, room=2 * K + W + 2, split_tokens=args.split_tokens)
+    # capacity: the initial length plus every step this run takes (graph mode runs K replays and K eager steps)
+    room = (2 * K if args.graph else K) + W + 2
+    if args.capacity:
+        if args.capacity < wl.T + room:
+            sys.exit("--capacity must be at least %d for this run" % (wl.T + room))
+        room = args.capacity - wl.T
+    sess = DecodeSession(wl, room=room, split_tokens=args.split_tokens)
     lk.lckv_set_load_policy(sess.h, args.load_policy)
     units = []
     if not args.no_cpu_baseline:
@@ -161,10 +173,17 @@ def main():
     kv = sess.fill(units)
     q, k_new, v_new = synth.step_inputs(wl, sess.n_slots, device="cuda")
     out = torch.empty_like(q)
+    if args.chain:
+        if args.graph:
+            sys.exit("--chain and --graph are separate modes")
+        q_seed, q = q, torch.empty_like(q)
+        one_step = lambda: sess.step_chained(q_seed, k_new, v_new, q, out)
+    else:
+        one_step = lambda: sess.step(q, k_new, v_new, out)
 
     base = None
     # first (untimed) step doubles as the check against the oracle
-    sess.step(q, k_new, v_new, out)
+    one_step()
     torch.cuda.synchronize()
     if units:
         base = cpu_baseline(sess, units, kv, q, k_new, v_new, out)
@@ -176,7 +195,7 @@ def main():
             sys.exit("GPU output disagrees with the oracle: %r" % base)
     del kv
     for _ in range(max(W - 1, 0)):
-        sess.step(q, k_new, v_new, out)
+        one_step()
     torch.cuda.synchronize()
 
     first_timed = 1 + max(W - 1, 0)
@@ -199,7 +218,7 @@ def main():
     torch.cuda.synchronize()
     te0 = time.perf_counter()
     for _ in range(0 if args.graph and sess.steps_left < K else K):
-        sess.step(q, k_new, v_new, out)
+        one_step()
     torch.cuda.synchronize()
     te1 = time.perf_counter()
     if not args.graph:
@@ -241,7 +260,7 @@ def main():
         "metric": METRIC.get(args.workload, "decode attention tokens/s (all layers, %s)" % wl.name),
         "value": wl.B / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.dtype, "data": "synthetic", "launch": "hip-graph replay" if args.graph else "eager",
+        "dtype": wl.dtype, "data": "synthetic", "launch": "hip-graph replay" if args.graph else ("eager, chained layers" if args.chain else "eager"),
         "config": {"workload": "%s: L=%d w=%d Hq=%d Hkv=%d D=%d B=%d T=%s%s" % (
             wl.name, wl.L, wl.w, wl.Hq, wl.Hkv, wl.D, wl.B,
             wl.T if wl.T_min is None else "U[%d,%d]" % (wl.T_min, wl.T), " paged16" if wl.paged else ""),

@@ -94,6 +94,12 @@ typedef struct lckv_config {
 /* Bytes of device storage a cache with this config needs (all slots).  Host only. */
 int lckv_cache_bytes(const lckv_config *cfg, size_t *bytes);
 
+/* Footprint planner: the largest number of sequences of cfg->T_max positions (contiguous layout; cfg->B_max is
+ * ignored) whose caches fit in budget_bytes.  The cache size is slots * B * T * 2 * Hkv * D * elem, so the gain
+ * over a standard transformer (all layers warmup) is L / slots - the memory side of the paper's batch-size
+ * claims (Section 3.1, Table 1).  Host only. */
+int lckv_plan_max_batch(const lckv_config *cfg, size_t budget_bytes, int32_t *max_batch);
+
 /* Build the pairing table of Section 2.1 from cfg->warmup_mask and bind the caller's device storage
  * (kv_storage, 256-byte aligned, at least lckv_cache_bytes; NOT cleared, NOT freed by the library).
  * Allocates the handle and small device tables.  All config errors are found before any GPU call. */

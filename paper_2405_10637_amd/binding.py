@@ -24,7 +24,7 @@ LCKV_DEV_ERR_CAPACITY, LCKV_DEV_ERR_BLOCK = 1, 2
 LCKV_LOAD_AUTO, LCKV_LOAD_TEMPORAL, LCKV_LOAD_NONTEMPORAL = 0, 1, 2
 
 EXPORTS = [
-    "lckv_cache_bytes", "lckv_cache_alloc", "lckv_cache_free", "lckv_cache_set_block_table", "lckv_n_slots",
+    "lckv_cache_bytes", "lckv_plan_max_batch", "lckv_cache_alloc", "lckv_cache_free", "lckv_cache_set_block_table", "lckv_n_slots",
     "lckv_kv_slot", "lckv_slot_producer", "lckv_append_kv", "lckv_decode_attention", "lckv_step",
     "lckv_workspace_bytes", "lckv_set_split_tokens", "lckv_set_load_policy", "lckv_cache_load_dense", "lckv_cache_read",
     "lckv_last_device_error", "lckv_profile_enable", "lckv_profile_read", "lckv_profile_launch_ms",
@@ -62,6 +62,7 @@ def lib():
         vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
         cfgp = ctypes.POINTER(lckv_config)
         L.lckv_cache_bytes.argtypes = [cfgp, ctypes.POINTER(sz)]
+        L.lckv_plan_max_batch.argtypes = [cfgp, sz, ctypes.POINTER(i32)]
         L.lckv_cache_alloc.argtypes = [cfgp, vp, sz, ctypes.POINTER(vp)]
         L.lckv_cache_free.argtypes = [vp]
         L.lckv_cache_set_block_table.argtypes = [vp, vp, i32]
@@ -128,6 +129,12 @@ def make_config(L, Hq, Hkv, D, dtype, B_max, T_max, warmup_mask, page_size=0, nu
 def lckv_cache_bytes(cfg: lckv_config) -> int:
     out = ctypes.c_size_t(0)
     _check(lib().lckv_cache_bytes(ctypes.byref(cfg), ctypes.byref(out)), "lckv_cache_bytes")
+    return out.value
+
+
+def lckv_plan_max_batch(cfg: lckv_config, budget_bytes: int) -> int:
+    out = ctypes.c_int32(0)
+    _check(lib().lckv_plan_max_batch(ctypes.byref(cfg), budget_bytes, ctypes.byref(out)), "lckv_plan_max_batch")
     return out.value
 
 

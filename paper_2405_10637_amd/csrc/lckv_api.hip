@@ -188,6 +188,12 @@ int attention_impl(lckv_cache *c, int layer, const void *q, void *out, const int
     // K/V of one layer's pass: B * n * 2 * Hkv * D * elem bytes.  Past the size of the last-level cache nothing
     // of it survives until the next layer reads the slot again, and the nontemporal hint makes the stream faster.
     const double pass_bytes = (double)B * max_n * 2.0 * cfg.Hkv * cfg.D * elem_bytes(cfg.dtype);
+    p.unit_mul = 1;
+    for (int prime : {2731, 1571, 7919, 104729})  // the first that does not divide the number of units
+        if (((int64_t)B * cfg.Hkv) % prime != 0) {
+            p.unit_mul = prime;
+            break;
+        }
     p.nontemporal = c->load_policy == LCKV_LOAD_NONTEMPORAL ||
                     (c->load_policy == LCKV_LOAD_AUTO && pass_bytes > kLastLevelCacheBytes);
 
@@ -222,6 +228,21 @@ int lckv_cache_bytes(const lckv_config *cfg, size_t *bytes) {
     if (rc != LCKV_OK) return rc;
     Geometry g = geometry(*cfg);
     *bytes = g.slot_bytes * (size_t)g.n_slots;
+    return LCKV_OK;
+}
+
+int lckv_plan_max_batch(const lckv_config *cfg, size_t budget_bytes, int32_t *max_batch) {
+    if (!max_batch) return LCKV_ERR_NULL;
+    if (!cfg) return LCKV_ERR_NULL;
+    lckv_config one = *cfg;
+    one.B_max = 1;
+    int rc = check_config(&one);
+    if (rc != LCKV_OK) return rc;
+    if (one.page_size != 0) return LCKV_ERR_CONFIG;
+    Geometry g = geometry(one);
+    size_t per_sequence = g.slot_bytes * (size_t)g.n_slots;
+    size_t n = budget_bytes / per_sequence;
+    *max_batch = n > 65535 ? 65535 : (int32_t)n;
     return LCKV_OK;
 }
 

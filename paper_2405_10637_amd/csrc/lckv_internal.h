@@ -80,6 +80,7 @@ struct AttnParams {
     int32_t n_splits;
     float scale_log2e;          // scale * log2(e)
     int32_t nontemporal;        // 1: read K/V with the nontemporal hint (stream larger than the caches)
+    int32_t unit_mul;           // launch order -> (sequence, kv head): unit = (id * unit_mul) mod (B * Hkv), coprime
 };
 
 hipError_t launch_attn_bf16(const AttnParams &p, int D, hipStream_t s);

@@ -103,3 +103,29 @@ class DecodeSession:
             n = self.lens0.astype(np.int64) + step_index + self.kv_slot[l][1]
             tot += int(n.sum()) * per_key
         return tot
+
+    def step_chained(self, q_seed, k_new, v_new, q_work, out):
+        """One decode step through the per-layer entry points with the model's layer-to-layer dependency made
+        physical: layer l's query is q_seed[l] + out[l-1] (the residual stream carries layer l-1's attention
+        output into layer l's query; Section 2.1, "bottom-up computation"), so no layer can start before the
+        previous one has finished.  q_work receives the queries actually used.  The adds are plain torch ops on
+        the same stream; appends and attention go through lckv_append_kv / lckv_decode_attention."""
+        assert self.steps_left > 0, "cache capacity used up"
+        wl = self.wl
+        for l in range(wl.L):
+            q_work[l].copy_(q_seed[l])
+            if l > 0:
+                q_work[l].add_(out[l - 1])
+            slot, vis = self.kv_slot[l]
+            mine = [s for s in range(self.n_slots) if self.producer[s] == l]
+            if vis:      # a warmup layer sees itself: its K/V go in first
+                for s in mine:
+                    lk.lckv_append_kv(self.h, l, k_new[s], v_new[s], self.lens, wl.B)
+            lk.lckv_decode_attention(self.h, l, q_work[l], out[l], self.lens, None, wl.B, self.max_len,
+                                     self.workspace)
+            if not vis:  # the shared slot's new K/V are invisible to this step's condensed layers
+                for s in mine:
+                    lk.lckv_append_kv(self.h, l, k_new[s], v_new[s], self.lens, wl.B)
+        self.lens.add_(1)
+        self.max_len += 1
+        self.steps_left -= 1
