@@ -279,6 +279,57 @@ int lckv_oracle_step(int L, int Hq, int Hkv, int D, int B, int64_t T_cap,
                                       out, 0, 0, threads);
 }
 
+/*
+ * Attention of ALL prompt tokens of one layer in one pass, as used by the
+ * parallel computation graph of Section 2.2 and by the iterative prompt
+ * encoding of Section 2.3: token i of sequence b attends to the K/V at
+ * positions j < i of the slot it is paired with (condensed layer: the
+ * diagonal is masked, the K/V are the top layer's from the PREVIOUS iteration)
+ * or j <= i (warmup layer: standard causal attention on this iteration's own
+ * K/V).  Token 0 of a condensed layer has nothing to attend to: zero output
+ * (zero dummy K/V).  Rows i >= lens[b] are zero.
+ *
+ *   Kc, Vc  one slot, [B][T_cap][Hkv][D] float, positions 0..lens[b]-1 filled
+ *   q       [B][S][Hq][D],   out  [B][S][Hq][D] double
+ * Returns the thread count used, or -1 on a bad argument.
+ */
+int lckv_oracle_prefill_attention(int Hq, int Hkv, int D, int B, int64_t S,
+                                  int64_t T_cap, const float *Kc,
+                                  const float *Vc, const int32_t *lens,
+                                  int self_visible, double scale,
+                                  const float *q, double *out, int threads)
+{
+    if (Hq <= 0 || Hkv <= 0 || D <= 0 || B <= 0 || S <= 0 || T_cap < S ||
+        Hq % Hkv != 0)
+        return -1;
+    for (int b = 0; b < B; ++b)
+        if (lens[b] < 0 || lens[b] > S) return -1;
+    const int G = Hq / Hkv;
+    const int64_t row = (int64_t)Hkv * D;
+    int used = 1;
+#ifdef _OPENMP
+    if (threads <= 0) threads = omp_get_max_threads();
+    used = threads;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads)
+#endif
+    for (int64_t bi = 0; bi < (int64_t)B * S; ++bi) {
+        int b = (int)(bi / S);
+        int64_t i = bi % S;
+        for (int h = 0; h < Hq; ++h) {
+            double *o = out + ((bi * Hq) + h) * D;
+            if (i >= lens[b]) {
+                for (int d = 0; d < D; ++d) o[d] = 0.0;
+                continue;
+            }
+            int64_t n = i + (self_visible ? 1 : 0);
+            int64_t base = (int64_t)b * T_cap * row + (int64_t)(h / G) * D;
+            lckv_oracle_attend(q + ((bi * Hq) + h) * D, Kc + base, Vc + base,
+                               n, row, D, scale, o, NULL);
+        }
+    }
+    return used;
+}
+
 int lckv_oracle_max_threads(void)
 {
 #ifdef _OPENMP

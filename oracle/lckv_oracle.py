@@ -71,6 +71,9 @@ def _load():
             ctypes.c_int64, u8p, ctypes.c_int, ctypes.c_double, f32p, f32p, i32p, f32p, f32p, f32p, f64p,
             ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
         lib.lckv_oracle_step_streaming.restype = ctypes.c_int
+        lib.lckv_oracle_prefill_attention.argtypes = [ctypes.c_int] * 4 + [
+            ctypes.c_int64, ctypes.c_int64, f32p, f32p, i32p, ctypes.c_int, ctypes.c_double, f32p, f64p, ctypes.c_int]
+        lib.lckv_oracle_prefill_attention.restype = ctypes.c_int
         lib.lckv_oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -175,4 +178,24 @@ def step(warm, Kc, Vc, lens, q, k_new, v_new, scale: float, rule: int = PAIR_TOP
         rc = _load().lckv_oracle_step(*args, threads)
     if rc < 0:
         raise ValueError("lckv_oracle_step failed with code %d" % rc)
+    return out, int(rc)
+
+
+def prefill_attention(Kc, Vc, lens, q, self_visible: bool, scale: float, threads: int = 0):
+    """All prompt tokens of one layer at once (Sections 2.2 and 2.3): token i attends to positions j < i of the
+    slot (condensed layer) or j <= i (warmup layer).  Kc, Vc: one slot, float32 [B][T_cap][Hkv][D];
+    lens: int32 [B] prompt lengths; q: [B][S][Hq][D].  Returns (out float64 [B][S][Hq][D], threads used)."""
+    Kc, Vc = _f32(Kc), _f32(Vc)
+    B, T_cap, Hkv, D = Kc.shape
+    assert Vc.shape == Kc.shape
+    q = _f32(q)
+    S, Hq = q.shape[1], q.shape[2]
+    assert q.shape == (B, S, Hq, D)
+    lens = np.ascontiguousarray(lens, dtype=np.int32)
+    out = np.zeros((B, S, Hq, D), np.float64)
+    rc = _load().lckv_oracle_prefill_attention(Hq, Hkv, D, B, S, T_cap, _p(Kc, ctypes.c_float), _p(Vc, ctypes.c_float),
+                                               _p(lens, ctypes.c_int32), int(bool(self_visible)), float(scale),
+                                               _p(q, ctypes.c_float), _p(out, ctypes.c_double), threads)
+    if rc < 0:
+        raise ValueError("lckv_oracle_prefill_attention: bad argument")
     return out, int(rc)

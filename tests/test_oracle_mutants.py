@@ -7,6 +7,7 @@ import pytest
 
 from oracle import lckv_oracle as orc
 import test_oracle_pins as pins
+import test_oracle_prefill_pins as prefill_pins
 
 SRC = os.path.join(os.path.dirname(orc.__file__), "lckv_oracle.c")
 
@@ -34,9 +35,13 @@ MUTANTS = {
     "sinks not kept": ("int64_t j = i < sink ? i :", "int64_t j = i < sink ? sink + i :"),
     "sink window policy ignored": ("if (window > 0 && n > sink + window) {", "if (0 && n > sink + window) {"),
     "kept values taken from K": ("memcpy(Vk + i * D, Vc + base", "memcpy(Vk + i * D, Kc + base"),
+    "prefill: diagonal not masked": ("int64_t n = i + (self_visible ? 1 : 0);", "int64_t n = i + 1;"),
+    "prefill: warmup layer misses itself": ("int64_t n = i + (self_visible ? 1 : 0);", "int64_t n = i;"),
+    "prefill: rows past the prompt computed": ("if (i >= lens[b]) {", "if (0) {"),
+    "prefill: gqa heads interleaved": ("(int64_t)(h / G) * D;", "(int64_t)(h % Hkv) * D;"),
 }
 
-PIN_FUNCS = [getattr(pins, n) for n in dir(pins) if n.startswith("test_")]
+PIN_FUNCS = [getattr(mod, n) for mod in (pins, prefill_pins) for n in dir(mod) if n.startswith("test_")]
 
 
 def _run_all_pins():
