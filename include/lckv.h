@@ -141,6 +141,21 @@ int lckv_decode_attention(lckv_cache *cache, int32_t layer, const void *q, void 
                           const int32_t *dev_seq_lens, const uint8_t *warmup_mask, int32_t B,
                           int32_t max_len_hint, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Attention of all prompt tokens of one layer in one pass, for the parallel computation of Section 2.2 and the
+ * iterative prompt encoding of Section 2.3 (m + b iterations over the whole prompt, each pairing the condensed
+ * layers with the top layer's K/V of the previous iteration, zeros before the first):
+ *   out[b][i][h] = softmax_j(scale * <q[b][i][h], K[slot][b][j][h/G]>) . V[slot][b][j][h/G]
+ * over j < i for a condensed layer (diagonal masked; token 0 sees nothing: zero vector) and j <= i for a warmup
+ * layer, for i < prompt_len_b; rows i >= prompt_len_b are written as zeros.  The K/V are read from the cache:
+ * the caller first imports them with lckv_cache_load_dense - a warmup layer's own K/V of this iteration before
+ * its attention, the top layer's K/V into the shared slot at the END of an iteration - so after the last
+ * iteration the cache holds the prompt and decoding can start.  q, out: device [B][S][Hq][D]; dev_prompt_lens:
+ * device int32[B], each <= S; S <= capacity.  Not available with the sink + window policy.  Only enqueues. */
+int lckv_prefill_attention(lckv_cache *cache, int32_t layer, const void *q, void *out,
+                           const int32_t *dev_prompt_lens, int32_t B, int32_t S, void *hip_stream);
+/* Tuning knob of the bf16 prefill kernel: 16-position query blocks per wave, 2 or 4 (0 = default).  Host only. */
+int lckv_set_prefill_tile(lckv_cache *cache, int32_t query_blocks_per_wave);
+
 /* The whole step: layers in index order (layer l+1 starts after layer l has finished: in the model its query
  * depends on layer l's output); a warmup layer's K/V are appended just before its attention (it sees itself),
  * the shared slot's new K/V just after the attention of the condensed layer that produces them (the diagonal is

@@ -25,7 +25,8 @@ LCKV_LOAD_AUTO, LCKV_LOAD_TEMPORAL, LCKV_LOAD_NONTEMPORAL = 0, 1, 2
 
 EXPORTS = [
     "lckv_cache_bytes", "lckv_plan_max_batch", "lckv_cache_alloc", "lckv_cache_free", "lckv_cache_set_block_table", "lckv_n_slots",
-    "lckv_kv_slot", "lckv_slot_producer", "lckv_append_kv", "lckv_decode_attention", "lckv_step",
+    "lckv_kv_slot", "lckv_slot_producer", "lckv_append_kv", "lckv_decode_attention", "lckv_prefill_attention",
+    "lckv_set_prefill_tile", "lckv_step",
     "lckv_workspace_bytes", "lckv_set_split_tokens", "lckv_set_load_policy", "lckv_cache_load_dense", "lckv_cache_read",
     "lckv_last_device_error", "lckv_profile_enable", "lckv_profile_read", "lckv_profile_launch_ms",
     "lckv_hbm_read_probe", "lckv_strerror",
@@ -71,7 +72,9 @@ def lib():
         L.lckv_slot_producer.argtypes = [vp, i32, ctypes.POINTER(i32)]
         L.lckv_append_kv.argtypes = [vp, i32, vp, vp, vp, i32, vp]
         L.lckv_decode_attention.argtypes = [vp, i32, vp, vp, vp, vp, i32, i32, vp, sz, vp]
-        L.lckv_step.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
+        L.lckv_prefill_attention.argtypes = [vp, i32, vp, vp, vp, i32, i32, vp]
+        L.lckv_set_prefill_tile.argtypes = [vp, i32]
+        L.lckv_step.argtypes =[vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
         L.lckv_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
         L.lckv_set_split_tokens.argtypes = [vp, i32]
         L.lckv_set_load_policy.argtypes = [vp, i32]
@@ -187,6 +190,15 @@ def lckv_decode_attention(cache: int, layer: int, q, out, dev_seq_lens, warmup_m
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lckv_decode_attention(cache, layer, _ptr(q), _ptr(out), _ptr(dev_seq_lens), mask, B, max_len_hint,
                                        _ptr(workspace), workspace_bytes, _stream(stream)), "lckv_decode_attention")
+
+
+def lckv_prefill_attention(cache: int, layer: int, q, out, dev_prompt_lens, B: int, S: int, stream=None):
+    _check(lib().lckv_prefill_attention(cache, layer, _ptr(q), _ptr(out), _ptr(dev_prompt_lens), B, S,
+                                        _stream(stream)), "lckv_prefill_attention")
+
+
+def lckv_set_prefill_tile(cache: int, query_blocks_per_wave: int):
+    _check(lib().lckv_set_prefill_tile(cache, query_blocks_per_wave), "lckv_set_prefill_tile")
 
 
 def lckv_step(cache: int, q_all, k_new_all, v_new_all, out_all, dev_seq_lens, B: int, max_len_hint: int,

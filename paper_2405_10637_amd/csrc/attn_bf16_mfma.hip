@@ -13,26 +13,9 @@
 // The loads of a tile never sit under a branch: a page past the end of the split (or with a bad block-table
 // entry) is redirected to a page that is certainly mapped and its contribution is dropped, so the compiler can
 // keep the next tile's loads in flight while the current tile is consumed.
-#include "lckv_internal.h"
+#include "bf16_mfma_common.h"
 
 namespace lckv {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(2))) float floatx2;
-typedef __attribute__((ext_vector_type(4))) float floatx4;
-typedef __attribute__((ext_vector_type(4))) short shortx4;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-
-constexpr float kNegInf = -__builtin_huge_valf();
-
-__device__ __forceinline__ float xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask, 64)); }
-
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-    floatx2 f = {a, b};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));  // v_cvt_pk_bf16_f32, RNE
-}
 
 template <int D, int NP>
 struct Tile {
@@ -40,14 +23,6 @@ struct Tile {
     u32x4 v[NP][D / 32];
     int page[NP];  // wave-uniform: page number, or -1 if what was loaded must be ignored
 };
-
-// Issue the loads of NP consecutive pages starting at `pg` for (b, g).  `pg`, `pg_end` are wave-uniform.
-template <bool NT>
-__device__ __forceinline__ u32x4 load16(const char *p) {
-    // NT: the nontemporal hint.  A stream that is read once and is far larger than the caches is fetched
-    // measurably faster with it on MI355X (about 7.1 instead of 6.3 TB/s for a pure read).
-    return NT ? __builtin_nontemporal_load((const u32x4 *)p) : *(const u32x4 *)p;
-}
 
 // The pages of a split, pg_begin .. pg_begin + n_pages - 1, are visited in rotated order: visit number `it` reads
 // page pg_begin + (it + rot) mod n_pages.  `it`, `rot`, `n_pages` are wave-uniform, 0 <= rot < n_pages.

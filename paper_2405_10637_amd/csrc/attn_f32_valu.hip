@@ -29,23 +29,16 @@ __device__ __forceinline__ float row_sum16(float x) {
     return x;
 }
 
+// One workgroup's work: query row `row` of p.q / p.out (head h, reading kv head h / G of sequence b) over the keys
+// [split * split_tokens, ...) of its n visible keys.
 template <int D>
-__global__ __launch_bounds__(kWaves * 64) void attn_f32_kernel(AttnParams p) {
+__device__ __forceinline__ void attend_row_f32(const AttnParams &p, int split, int h, int b, int n, int64_t row) {
     constexpr int NV = D / 64;  // float4 per lane per row
-    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int g = h / p.G;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kq = lane >> 4, r = lane & 15;  // which of the wave's 4 keys / 16-byte column of the row
-
-    int n = p.seq_lens[b] + p.self_visible;
-    if (n > p.max_n) {
-        n = p.max_n;
-        if (tid == 0 && !p.clamp_is_policy) atomicOr(p.dev_err, LCKV_DEV_ERR_CAPACITY);
-    }
-    if (n < 0) n = 0;
     const int k_begin = split * p.split_tokens;
     const int k_end = min(n, k_begin + p.split_tokens);
-    const int64_t row = (int64_t)b * p.Hq + h;
     float *out = (float *)p.out + row * D;
 
     if (k_begin >= k_end) {
@@ -141,6 +134,33 @@ __global__ __launch_bounds__(kWaves * 64) void attn_f32_kernel(AttnParams p) {
     }
 }
 
+// Decode: one query token per sequence.
+template <int D>
+__global__ __launch_bounds__(kWaves * 64) void attn_f32_kernel(AttnParams p) {
+    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    int n = p.seq_lens[b] + p.self_visible;
+    if (n > p.max_n) {
+        n = p.max_n;
+        if (threadIdx.x == 0 && !p.clamp_is_policy) atomicOr(p.dev_err, LCKV_DEV_ERR_CAPACITY);
+    }
+    if (n < 0) n = 0;
+    attend_row_f32<D>(p, split, h, b, n, (int64_t)b * p.Hq + h);
+}
+
+// Prefill (all prompt tokens of a layer at once, Sections 2.2 and 2.3 of the LCKV paper): one workgroup per
+// (token i, head, sequence); token i sees i keys, or i + 1 in a warmup layer; rows past the prompt are zero.
+template <int D>
+__global__ __launch_bounds__(kWaves * 64) void prefill_f32_kernel(AttnParams p, int S) {
+    const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    int len = p.seq_lens[b];
+    if (len > p.max_n) {
+        len = p.max_n;
+        if (threadIdx.x == 0) atomicOr(p.dev_err, LCKV_DEV_ERR_CAPACITY);
+    }
+    const int n = i < len ? i + p.self_visible : 0;  // n = 0 writes the zero vector
+    attend_row_f32<D>(p, 0, h, b, n, ((int64_t)b * S + i) * p.Hq + h);
+}
+
 }  // namespace
 
 hipError_t launch_attn_f32(const AttnParams &p, int D, hipStream_t s) {
@@ -149,6 +169,16 @@ hipError_t launch_attn_f32(const AttnParams &p, int D, hipStream_t s) {
         hipLaunchKernelGGL((attn_f32_kernel<128>), grid, block, 0, s, p);
     else
         hipLaunchKernelGGL((attn_f32_kernel<64>), grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+// p: n_splits = 1, split_tokens >= S, max_n = min(S, capacity), seq_lens = prompt lengths.
+hipError_t launch_prefill_f32(const AttnParams &p, int S, int D, hipStream_t s) {
+    dim3 grid(S, p.Hq, p.B), block(kWaves * 64);
+    if (D == 128)
+        hipLaunchKernelGGL((prefill_f32_kernel<128>), grid, block, 0, s, p, S);
+    else
+        hipLaunchKernelGGL((prefill_f32_kernel<64>), grid, block, 0, s, p, S);
     return hipGetLastError();
 }
 

@@ -273,6 +273,7 @@ int lckv_cache_alloc(const lckv_config *cfg, void *kv_storage, size_t kv_bytes, 
     c->capacity = cfg->page_size ? 0 : g.pages_per_seq * kPage;
     c->forced_split_tokens = 0;
     c->load_policy = LCKV_LOAD_AUTO;
+    c->prefill_query_blocks = 0;  // 0: chosen per head dimension at launch
     c->scale = cfg->scale > 0.f ? cfg->scale : 1.0f / sqrtf((float)cfg->D);
     c->profiling = false;
     c->ev_used = 0;
@@ -355,6 +356,49 @@ int lckv_decode_attention(lckv_cache *c, int32_t layer, const void *q, void *out
     if (!aligned(q, 16) || !aligned(out, 16) || !aligned(dev_seq_lens, 4)) return LCKV_ERR_ALIGN;
     return attention_impl(c, layer, q, out, dev_seq_lens, B, max_len_hint, workspace, workspace_bytes,
                           (hipStream_t)hip_stream);
+}
+
+int lckv_prefill_attention(lckv_cache *c, int32_t layer, const void *q, void *out, const int32_t *dev_prompt_lens,
+                           int32_t B, int32_t S, void *hip_stream) {
+    if (!valid(c) || !q || !out || !dev_prompt_lens) return LCKV_ERR_NULL;
+    if (layer < 0 || layer >= c->cfg.L) return LCKV_ERR_LAYER;
+    if (c->cfg.window_tokens > 0) return LCKV_ERR_CONFIG;  // prompts are encoded into a cache that keeps everything
+    if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
+    if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
+    if (S < 1 || S > c->capacity) return LCKV_ERR_LENGTH;
+    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(dev_prompt_lens, 4)) return LCKV_ERR_ALIGN;
+    const lckv_config &cfg = c->cfg;
+    AttnParams p;
+    p.slot = slot_view(c, c->kv_slot[layer]);
+    p.q = q;
+    p.out = out;
+    p.seq_lens = dev_prompt_lens;
+    p.part_o = nullptr;
+    p.part_ml = nullptr;
+    p.dev_err = c->dev_err;
+    p.B = B;
+    p.Hq = cfg.Hq;
+    p.Hkv = cfg.Hkv;
+    p.G = cfg.Hq / cfg.Hkv;
+    p.self_visible = c->self_visible[layer];
+    p.max_n = S;
+    p.clamp_is_policy = 0;
+    p.split_tokens = (S + 63) / 64 * 64;
+    p.n_splits = 1;
+    p.scale_log2e = c->scale * 1.4426950408889634f;
+    p.nontemporal = 0;
+    p.unit_mul = 1;
+    hipError_t e = cfg.dtype == LCKV_BF16
+                       ? launch_prefill_bf16(p, S, cfg.D, c->prefill_query_blocks, (hipStream_t)hip_stream)
+                       : launch_prefill_f32(p, S, cfg.D, (hipStream_t)hip_stream);
+    return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
+}
+
+int lckv_set_prefill_tile(lckv_cache *c, int32_t query_blocks_per_wave) {
+    if (!valid(c)) return LCKV_ERR_NULL;
+    if (query_blocks_per_wave != 0 && query_blocks_per_wave != 2 && query_blocks_per_wave != 4) return LCKV_ERR_CONFIG;
+    c->prefill_query_blocks = query_blocks_per_wave;
+    return LCKV_OK;
 }
 
 int lckv_step(lckv_cache *c, const void *q_all, const void *k_new_all, const void *v_new_all, void *out_all,

@@ -85,6 +85,8 @@ struct AttnParams {
 
 hipError_t launch_attn_bf16(const AttnParams &p, int D, hipStream_t s);
 hipError_t launch_attn_f32(const AttnParams &p, int D, hipStream_t s);
+hipError_t launch_prefill_f32(const AttnParams &p, int S, int D, hipStream_t s);
+hipError_t launch_prefill_bf16(const AttnParams &p, int S, int D, int query_blocks, hipStream_t s);
 hipError_t launch_combine(const AttnParams &p, int D, int dtype, hipStream_t s);
 hipError_t launch_append(const SlotView &v, const void *k_new, const void *v_new, const int32_t *seq_lens,
                          int B, int D, int dtype, int32_t *dev_err, hipStream_t s);
@@ -113,6 +115,7 @@ struct lckv_cache {
     int32_t capacity;
     int32_t forced_split_tokens;
     int32_t load_policy;          // LCKV_LOAD_*
+    int32_t prefill_query_blocks; // 16-position blocks per wave in the bf16 prefill kernel (2 or 4)
     int32_t *dev_err;
     float scale;
     // kernel timing

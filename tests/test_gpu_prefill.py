@@ -1,0 +1,137 @@
+"""GPU parity of lckv_prefill_attention (all prompt tokens of a layer in one pass, Sections 2.2 and 2.3) against
+the oracle, element by element: ragged prompt lengths including 0 and 1, prompt ends inside a page, more rows
+than one workgroup covers, condensed and warmup layers, GQA, contiguous and paged caches, bf16 and fp32; then a
+whole iterative prompt encoding followed by decode steps."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lckv_oracle as orc
+from paper_2405_10637_amd import binding as lk
+from paper_2405_10637_amd import synth
+
+from gpu_harness import GpuCache, check_close, to_f32_numpy
+
+pytestmark = pytest.mark.gpu
+
+
+def run_prefill(wl, S, lens, tile=0, T_cap=None):
+    print("prefill case", wl.name, wl.dtype, "H", wl.Hq, wl.Hkv, "D", wl.D, "S", S, "lens", list(lens), "paged",
+          wl.paged, "tile", tile, flush=True)
+    lens = np.asarray(lens, np.int32)
+    T_cap = T_cap or S
+    with GpuCache(wl, T_cap, lens) as gc:
+        if tile:
+            lk.lckv_set_prefill_tile(gc.h, tile)
+        K, V = synth.logical_cache(wl, gc.n_slots, S)                # [slots][B][S][Hkv][D]
+        for s in range(gc.n_slots):
+            Kg, Vg = K[s].clone(), V[s].clone()
+            for b in range(wl.B):
+                Kg[b, lens[b]:] = float("nan")                       # what lies beyond the prompt is poison
+                Vg[b, lens[b]:] = float("nan")
+            gc.load_dense(s, Kg, Vg)
+        q = synth._normal((wl.L, wl.B, S, wl.Hq, wl.D), wl.sigma, wl.torch_dtype, wl.seed + 5)
+        qd = q.cuda()
+        scale = 1.0 / np.sqrt(wl.D)
+        worst = 0.0
+        for l in range(wl.L):
+            slot, vis = lk.lckv_kv_slot(gc.h, l)
+            out = torch.full((wl.B, S, wl.Hq, wl.D), float("nan"), dtype=wl.torch_dtype, device="cuda")
+            lk.lckv_prefill_attention(gc.h, l, qd[l], out, gc.lens, wl.B, S)
+            torch.cuda.synchronize()
+            want, _ = orc.prefill_attention(to_f32_numpy(K[slot]), to_f32_numpy(V[slot]), lens, to_f32_numpy(q[l]),
+                                            bool(vis), scale)
+            worst = max(worst, check_close(out, want, wl.dtype, "%s layer %d" % (wl.name, l)))
+            for b in range(wl.B):                                    # rows past the prompt are exact zeros
+                assert (out[b, lens[b]:] == 0).all()
+        assert gc.device_error() == 0
+    return worst
+
+
+def test_prefill_bf16_mha_d128_ragged():
+    wl = synth.Workload("p-mha128", "bf16", L=2, w=1, Hq=2, Hkv=2, D=128, B=5, T=300, sigma=1.0, seed=41, warm=(0,))
+    run_prefill(wl, 300, [300, 0, 1, 17, 150])
+
+
+def test_prefill_bf16_mha_d128_four_blocks_per_wave():
+    wl = synth.Workload("p-mha128-qb4", "bf16", L=2, w=1, Hq=2, Hkv=2, D=128, B=2, T=280, sigma=1.0, seed=42,
+                        warm=(0,))
+    run_prefill(wl, 280, [280, 33], tile=4)
+
+
+@pytest.mark.parametrize("tile", [2, 4])
+def test_prefill_bf16_gqa_d64_paged(tile):
+    wl = synth.Workload("p-gqa64", "bf16", L=3, w=1, Hq=8, Hkv=2, D=64, B=3, T=530, sigma=1.0, seed=43, paged=True)
+    run_prefill(wl, 530, [530, 257, 64], tile=tile, T_cap=544)
+
+
+def test_prefill_f32_d64_and_d128():
+    wl = synth.Workload("p-f32", "f32", L=2, w=1, Hq=4, Hkv=2, D=64, B=2, T=70, sigma=1.0, seed=44, warm=(0,))
+    run_prefill(wl, 70, [70, 19])
+    wl = synth.Workload("p-f32-128", "f32", L=2, w=1, Hq=2, Hkv=1, D=128, B=2, T=40, sigma=1.0, seed=45, paged=True)
+    run_prefill(wl, 40, [40, 0], T_cap=48)
+
+
+def test_prefill_argument_errors():
+    wl = synth.Workload("p-err", "bf16", L=2, w=0, Hq=2, Hkv=2, D=64, B=1, T=32, sigma=1.0, seed=46)
+    with GpuCache(wl, 32, np.array([8], np.int32)) as gc:
+        q = torch.zeros((1, 64, 2, 64), dtype=torch.bfloat16, device="cuda")
+        L = lk.lib()
+        st = torch.cuda.current_stream().cuda_stream or None
+        call = lambda layer, S, B=1: L.lckv_prefill_attention(gc.h, layer, q.data_ptr(), q.data_ptr(),
+                                                              gc.lens.data_ptr(), B, S, st)
+        assert call(0, 33) == lk.LCKV_ERR_LENGTH and call(0, 0) == lk.LCKV_ERR_LENGTH
+        assert call(2, 8) == lk.LCKV_ERR_LAYER and call(0, 8, B=2) == lk.LCKV_ERR_BATCH
+        assert L.lckv_prefill_attention(gc.h, 0, None, q.data_ptr(), gc.lens.data_ptr(), 1, 8, st) == lk.LCKV_ERR_NULL
+    with GpuCache(wl, 32, np.array([8], np.int32), sink=4, window=28) as gc:
+        assert L.lckv_prefill_attention(gc.h, 0, q.data_ptr(), q.data_ptr(), gc.lens.data_ptr(), 1, 8, st) == \
+            lk.LCKV_ERR_CONFIG
+
+
+def test_iterative_prompt_encoding_then_decode():
+    # Section 2.3 end to end on the attention path: a few iterations over the prompt (the shared slot holds the
+    # previous iteration's top-layer K/V, zeros before the first; warmup layers hold their own K/V of this
+    # iteration), then decode steps on the cache the last iteration left.  The same sequence of calls on the
+    # oracle: prefill_attention + step.
+    wl = synth.Workload("p-iter", "bf16", L=4, w=2, Hq=4, Hkv=2, D=64, B=3, T=90, sigma=1.0, seed=47)
+    S, iters = 90, 3
+    lens = np.array([90, 41, 16], np.int32)
+    T_cap = 96
+    scale = 1.0 / np.sqrt(wl.D)
+    with GpuCache(wl, T_cap, lens) as gc:
+        ns = gc.n_slots
+        Kf = np.zeros((ns, wl.B, T_cap, wl.Hkv, wl.D), np.float32)   # oracle's caches
+        Vf = np.zeros_like(Kf)
+        zeros = torch.zeros((wl.B, S, wl.Hkv, wl.D), dtype=torch.bfloat16)
+        for s in range(ns):
+            gc.load_dense(s, zeros, zeros)                            # zero dummy K/V before the first iteration
+        for it in range(iters):
+            q = synth._normal((wl.L, wl.B, S, wl.Hq, wl.D), 1.0, torch.bfloat16, 1000 + it)
+            kv = [(synth._normal((wl.B, S, wl.Hkv, wl.D), 1.0, torch.bfloat16, 2000 + 10 * it + s),
+                   synth._normal((wl.B, S, wl.Hkv, wl.D), 1.0, torch.bfloat16, 3000 + 10 * it + s)) for s in range(ns)]
+            pending = None
+            for l in range(wl.L):
+                slot, vis = lk.lckv_kv_slot(gc.h, l)
+                produces = lk.lckv_slot_producer(gc.h, slot) == l
+                if vis:                                               # warmup layer: own K/V of this iteration
+                    gc.load_dense(slot, *kv[slot])
+                    Kf[slot, :, :S], Vf[slot, :, :S] = to_f32_numpy(kv[slot][0]), to_f32_numpy(kv[slot][1])
+                elif produces:
+                    pending = slot                                    # visible from the next iteration on
+                out = torch.full((wl.B, S, wl.Hq, wl.D), float("nan"), dtype=torch.bfloat16, device="cuda")
+                lk.lckv_prefill_attention(gc.h, l, q[l].cuda(), out, gc.lens, wl.B, S)
+                torch.cuda.synchronize()
+                want, _ = orc.prefill_attention(Kf[slot], Vf[slot], lens, to_f32_numpy(q[l]), bool(vis), scale)
+                check_close(out, want, "bf16", "iteration %d layer %d" % (it, l))
+                if it == 0 and not vis:
+                    assert (out == 0).all()                           # attention over zero dummy K/V is zero
+            gc.load_dense(pending, *kv[pending])
+            Kf[pending, :, :S], Vf[pending, :, :S] = to_f32_numpy(kv[pending][0]), to_f32_numpy(kv[pending][1])
+        lens_o = lens.copy()
+        for step in range(3):                                         # decoding continues on the same cache
+            q, kn, vn = synth.step_inputs(wl, ns, step=step)
+            out = gc.step(q, kn, vn)
+            want, _ = orc.step(wl.warmup_mask, Kf, Vf, lens_o, to_f32_numpy(q), to_f32_numpy(kn), to_f32_numpy(vn),
+                               scale)
+            check_close(out, want, "bf16", "decode step %d after prompt encoding" % step)
+        assert gc.device_error() == 0
