@@ -120,6 +120,64 @@ def residency_sweep(steps, warmup):
                       "last_level_cache_MiB": 256, "rows": rows}))
 
 
+def prefill_bench(steps, warmup, tile):
+    """Prompt-encoding attention (lckv_prefill_attention, one condensed layer over the whole prompt), Llama-7B
+    shape, bf16: B=16 prompts of S=2048 tokens.  Compute-bound: reported against the bf16 matrix-core peak.
+    Checks a sample of rows against the oracle.  Prints one JSON line."""
+    import numpy as np
+    import torch
+    from oracle import lckv_oracle as orc
+    from paper_2405_10637_amd import binding as lk
+    from paper_2405_10637_amd import synth
+    from paper_2405_10637_amd.runner import DecodeSession
+
+    S = 2048
+    wl = synth.C3.with_(B=16, T=S, name="prefill-llama-7b-B16-S2048")
+    with DecodeSession(wl, room=16) as sess:
+        if tile:
+            lk.lckv_set_prefill_tile(sess.h, tile)
+        layer = 1                                    # a condensed layer: reads the shared slot, diagonal masked
+        slot, vis = sess.kv_slot[layer]
+        units = [(layer, b, h) for b in (0, wl.B - 1) for h in (0, 13, wl.Hq - 1)]
+        kv = sess.fill(units)
+        q = synth._normal((wl.B, S, wl.Hq, wl.D), wl.sigma, wl.torch_dtype, wl.seed + 9, device="cuda")
+        out = torch.empty_like(q)
+        run = lambda: lk.lckv_prefill_attention(sess.h, layer, q, out, sess.lens, wl.B, S)
+        run()
+        torch.cuda.synchronize()
+        err = ref = 0.0
+        rows = [0, 1, 15, 16, 17, 255, 256, 1023, S - 1]
+        for (_, b, h) in units:                       # oracle on sampled rows of sampled (sequence, head) pairs
+            Ku, Vu = kv[(layer, b, h)]
+            for i in rows:
+                want = orc.attend(q[b, i, h].float().cpu().numpy(), Ku[:i], Vu[:i], 1.0 / np.sqrt(wl.D))
+                got = out[b, i, h].float().cpu().numpy().astype(np.float64)
+                err, ref = max(err, float(np.abs(got - want).max())), max(ref, float(np.abs(want).max()))
+        if err > 2e-2 or err > 1e-2 * max(ref, 1e-3):
+            sys.exit("prefill output disagrees with the oracle: err %g, max expected %g" % (err, ref))
+        for _ in range(warmup):
+            run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        pairs = wl.B * wl.Hq * (S * (S - 1) // 2)                  # (query, key) pairs below the diagonal
+        flops = 4.0 * wl.D * pairs                                 # QK^T and PV, 2 flops per multiply-add
+        tflops = flops / (ms * 1e-3) / 1e12
+        print(json.dumps({
+            "metric": "prompt-encoding attention, one condensed layer (Llama-7B shape, B=16, S=2048)",
+            "value": wl.B * S / (ms * 1e-3), "unit": "prompt tokens/s per layer", "n_gpus": 1, "steps": steps,
+            "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": wl.name},
+            "roofline": {"bound": "mfma", "kernel": "prefill_bf16_kernel", "achieved": tflops, "peak": 2500.0,
+                         "unit": "TFLOP/s", "frac": tflops / 2500.0, "traffic": None},
+            "max_abs_err_vs_oracle": err, "max_abs_expected": ref}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -138,6 +196,9 @@ def main():
     ap.add_argument("--chain", action="store_true",
                     help="feed layer l's output into layer l+1's query (q[l+1] = q_seed[l+1] + out[l]) so the "
                          "layer-to-layer dependency of the model is physically real; per-layer entry points")
+    ap.add_argument("--prefill", action="store_true",
+                    help="instead of the decode benchmark: prompt-encoding attention of one layer (MFMA-bound)")
+    ap.add_argument("--prefill-tile", type=int, default=0, help="query blocks per wave in the prefill kernel (2|4)")
     ap.add_argument("--residency-sweep", action="store_true",
                     help="instead of the benchmark: effective bandwidth vs size of the shared slot (C2 shape)")
     args = ap.parse_args()
@@ -145,6 +206,8 @@ def main():
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
     if args.residency_sweep:
         return residency_sweep(args.steps, args.warmup)
+    if args.prefill:
+        return prefill_bench(args.steps, args.warmup, args.prefill_tile)
 
     import numpy as np
     import torch

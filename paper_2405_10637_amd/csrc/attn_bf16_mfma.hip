@@ -102,8 +102,7 @@ __device__ __forceinline__ void consume_tile(Tile<D, NP> &t, const bf16x8 (&qb)[
         smax = fmaxf(smax, fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])));
     }
     // the four lanes (kb = 0..3) of a query column share one running maximum
-    smax = xor_max(smax, 16);
-    smax = xor_max(smax, 32);
+    smax = column_max4(smax);
     float m_new = fmaxf(m, smax);  // finite: a page that is used always holds a visible key
     float mb = m_new * c;
     float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
@@ -238,8 +237,7 @@ __global__ __launch_bounds__(W * 64) void attn_bf16_kernel(AttnParams p) {
     }
 
     // denominators were kept per lane: add the four key quads of each column
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
+    l = column_sum4(l);
 
     // merge the four waves: (m, l, O) per query column through LDS
     __shared__ float sm_m[W][16];

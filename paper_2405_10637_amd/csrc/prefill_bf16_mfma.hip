@@ -133,8 +133,7 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(AttnParams p, int S) 
                     if (key0 + e >= n_col[x]) z[e] = kNegInf;
             }
             float smax = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
-            smax = xor_max(smax, 16);
-            smax = xor_max(smax, 32);
+            smax = column_max4(smax);
             const float m_new = fmaxf(m[x], smax);
             const float m_use = m_new == kNegInf ? 0.f : m_new;  // a column that has seen no key yet
             const float mb = m_use * cs;
@@ -193,8 +192,7 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(AttnParams p, int S) 
 #pragma unroll
     for (int x = 0; x < QB; ++x) {
         float L = l[x];
-        L += __shfl_xor(L, 16, 64);
-        L += __shfl_xor(L, 32, 64);
+        L = column_sum4(L);
         const int i = i_lo + 16 * x + c;
         if (i >= S) continue;
         const float inv = (i < len && L > 0.f) ? 1.f / L : 0.f;  // rows past the prompt, and a token that sees
