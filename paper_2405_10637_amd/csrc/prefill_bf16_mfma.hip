@@ -8,71 +8,66 @@
 // positions of one head instead of the heads of a group, and each column has its own number of visible keys:
 //   S^T[key][pos] = K_page . Q^T       (v_mfma_f32_16x16x32_bf16)
 //   O^T[d][pos]  += V_page^T . P^T     (v_mfma_f32_16x16x16_bf16)
-// A wave owns QB blocks of 16 positions, walks the key pages 0 .. diagonal once and applies every page to all its
-// blocks (a page loaded once feeds 16*QB queries); pages come straight from the cache in operand order, there is
-// no LDS and no merge between waves.  Compute-bound; K/V re-reads come from L2.
+// A workgroup of 4 waves owns 4 * QB blocks of 16 positions of one head (QB per wave) and walks the key pages
+// 0 .. diagonal once.  Pages are brought into LDS by direct global-to-LDS loads (global_load_lds_dwordx4; the
+// cache stores pages in operand order, so the LDS image needs no rearrangement and every wave reads its operands
+// with conflict-free ds_read_b128), two tiles of NPG pages in flight, and every page feeds all 64 * QB queries of
+// the workgroup.  No merge between waves.  Compute-bound; the K/V of a head (S * D * 4 bytes) stay in the L2 of
+// the XCD that runs all row chunks of that head.
 #include "bf16_mfma_common.h"
 
 namespace lckv {
 
 namespace {
 
-template <int D>
-struct PageRegs {
-    u32x4 k[D / 32];
-    u32x4 v[D / 32];
-};
+typedef __attribute__((address_space(1))) const void *GlobalPtr;
+typedef __attribute__((address_space(3))) void *LdsPtr;
 
-template <int D, bool PAGED>
-__device__ __forceinline__ void load_page(PageRegs<D> &r, const SlotView &sv, int b, int g, int pg, int lane_off,
-                                          int32_t *dev_err) {
-    constexpr int64_t kPair = 2 * kPage * D * 2;
-    int64_t idx;
-    if (PAGED) {
-        int32_t blk = sv.table[(int64_t)b * sv.max_blocks + pg];
-        if (blk < 0 || (int64_t)blk >= sv.num_blocks) {
-            if (lane_off == 0) atomicOr(dev_err, LCKV_DEV_ERR_BLOCK);
-            blk = 0;  // read something that exists; the result of this sequence is undefined, the error is raised
-        }
-        idx = (int64_t)blk * sv.Hkv + g;
-    } else {
-        idx = ((int64_t)b * sv.Hkv + g) * sv.pages_per_seq + pg;
-    }
-    const char *base = sv.base + idx * kPair + lane_off;
-#pragma unroll
-    for (int ks = 0; ks < D / 32; ++ks) r.k[ks] = load16<false>(base + ks * 1024);
-#pragma unroll
-    for (int dp = 0; dp < D / 32; ++dp) r.v[dp] = load16<false>(base + kPair / 2 + dp * 1024);
-}
-
-template <int D, int QB, bool PAGED>
+template <int D, int QB, int NPG, bool PAGED>
 __global__ __launch_bounds__(256) void prefill_bf16_kernel(AttnParams p, int S) {
-    constexpr int kRows = 16 * QB;  // query positions per wave
-    const int h = blockIdx.y, b = blockIdx.z;
+    constexpr int kRows = 16 * QB;                 // query positions per wave
+    constexpr int kPair = 2 * kPage * D * 2;       // bytes of a K page + V page
+    constexpr int kLoadsPerPage = kPair / 1024;    // 1 KiB per wave-wide load
+    constexpr int kLoadsPerWave = NPG * kLoadsPerPage / 4;
+    static_assert(NPG * kLoadsPerPage % 4 == 0, "a tile's loads must divide among the four waves");
+    __shared__ __attribute__((aligned(16))) char lds[2][NPG * kPair];
+
+    // Which (sequence, head, row chunk) this workgroup takes.  Workgroups are handed to the 8 XCDs round-robin
+    // by their launch index, and every XCD has an L2 of its own: the launch index is unfolded so that each XCD
+    // gets a contiguous range of tasks, i.e. all row chunks of a head (and the heads of one kv group) run on one
+    // XCD at about the same time and share that head's K/V pages in its L2.
+    constexpr int kXcd = 8;
+    const int n_chunks = (S + 4 * kRows - 1) / (4 * kRows);
+    const int total = n_chunks * p.Hq * p.B;
+    const int per_xcd = (total + kXcd - 1) / kXcd;
+    const int task = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
+    if (task >= total) return;
+    const int chunk = n_chunks - 1 - task % n_chunks;  // rows with the most keys first
+    const int h = (task / n_chunks) % p.Hq, b = task / (n_chunks * p.Hq);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, kb = lane >> 4;  // query position within a block / key quad
     const int g = h / p.G;
-    const int chunk = gridDim.x - 1 - blockIdx.x;  // rows with the most keys first
-    const int i_lo = (chunk * 4 + wave) * kRows;
-    if (i_lo >= S) return;
+    const int i_wg = chunk * 4 * kRows;       // first row of the workgroup
+    const int i_lo = i_wg + wave * kRows;     // first row of this wave
 
     int len = p.seq_lens[b];
     if (len > p.max_n) {
         len = p.max_n;
-        if (lane == 0) atomicOr(p.dev_err, LCKV_DEV_ERR_CAPACITY);
+        if (tid == 0) atomicOr(p.dev_err, LCKV_DEV_ERR_CAPACITY);
     }
     if (len < 0) len = 0;
     uint16_t *out = (uint16_t *)p.out;
     const int self = p.self_visible;
+    const bool active = i_lo < len;           // wave-uniform: this wave has rows inside the prompt
 
-    if (i_lo >= len) {  // none of this wave's rows belongs to the prompt: zero rows
+    if (!active) {  // rows past the prompt are zero
         for (int r = 0; r < kRows && i_lo + r < S; ++r) {
             uint32_t *o = (uint32_t *)(out + (((int64_t)b * S + i_lo + r) * p.Hq + h) * D);
             for (int e = lane; e < D / 2; e += 64) o[e] = 0u;
         }
-        return;
     }
+    if (i_wg >= len) return;  // uniform over the workgroup: nothing to attend
 
     // Q^T operands and the number of keys each column sees
     bf16x8 qb[QB][D / 32];
@@ -85,7 +80,7 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(AttnParams p, int S) 
 #pragma unroll
         for (int ks = 0; ks < D / 32; ++ks) {
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (i < S) v = *(const u32x4 *)(qp + ks * 64);
+            if (active && i < S) v = *(const u32x4 *)(qp + ks * 64);
             qb[x][ks] = __builtin_bit_cast(bf16x8, v);
         }
     }
@@ -101,20 +96,51 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(AttnParams p, int S) 
     }
     const float cs = p.scale_log2e;
     const int lane_off = lane * 16;
-    const int n_most = min(i_lo + kRows - 1 + self, len);  // keys seen by the last column of this wave
-    const int n_pages = (n_most + kPage - 1) / kPage;
+    // pages needed by the workgroup (its last row) and by this wave
+    const int n_pages_wg = (min(i_wg + 4 * kRows - 1 + self, len) + kPage - 1) / kPage;
+    const int n_pages = active ? (min(i_lo + kRows - 1 + self, len) + kPage - 1) / kPage : 0;
+    const int n_tiles = (n_pages_wg + NPG - 1) / NPG;
 
-    auto consume = [&](PageRegs<D> &r, int pg) {
+    // This wave's share of the loads of tile t: 1 KiB pieces wave, wave + 4, ... of the tile's NPG page pairs.
+    auto issue_tile = [&](int t) {
+#pragma unroll
+        for (int r = 0; r < kLoadsPerWave; ++r) {
+            const int piece = wave + 4 * r;
+            int pg = t * NPG + piece / kLoadsPerPage;
+            if (pg >= n_pages_wg) pg = n_pages_wg - 1;  // past the end: any mapped page, it is not used
+            int64_t idx;
+            if (PAGED) {
+                int32_t blk = p.slot.table[(int64_t)b * p.slot.max_blocks + pg];
+                if (blk < 0 || (int64_t)blk >= p.slot.num_blocks) {
+                    if (lane == 0) atomicOr(p.dev_err, LCKV_DEV_ERR_BLOCK);
+                    blk = 0;  // read something that exists; this sequence's result is undefined, the error is raised
+                }
+                idx = (int64_t)blk * p.slot.Hkv + g;
+            } else {
+                idx = ((int64_t)b * p.slot.Hkv + g) * p.slot.pages_per_seq + pg;
+            }
+            const char *src = p.slot.base + idx * kPair + (piece % kLoadsPerPage) * 1024 + lane_off;
+            // lane l's 16 bytes land at the LDS address + 16 * l
+            __builtin_amdgcn_global_load_lds((GlobalPtr)src, (LdsPtr)(&lds[t & 1][piece * 1024]), 16, 0, 0);
+        }
+    };
+
+    auto consume_page = [&](const char *page, int pg) {
+        u32x4 kr[D / 32], vr[D / 32];
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ++ks) kr[ks] = *(const u32x4 *)(page + ks * 1024 + lane_off);
+#pragma unroll
+        for (int dp = 0; dp < D / 32; ++dp) vr[dp] = *(const u32x4 *)(page + kPair / 2 + dp * 1024 + lane_off);
         if ((pg + 1) * kPage > len) {  // last, partly filled page of the prompt: clear stale values (0 * NaN)
             int nv = len - (pg * kPage + 4 * kb);
             uint32_t m01 = nv >= 2 ? 0xffffffffu : (nv == 1 ? 0x0000ffffu : 0u);
             uint32_t m23 = nv >= 4 ? 0xffffffffu : (nv == 3 ? 0x0000ffffu : 0u);
 #pragma unroll
             for (int dp = 0; dp < D / 32; ++dp) {
-                r.v[dp][0] &= m01;
-                r.v[dp][1] &= m23;
-                r.v[dp][2] &= m01;
-                r.v[dp][3] &= m23;
+                vr[dp][0] &= m01;
+                vr[dp][1] &= m23;
+                vr[dp][2] &= m01;
+                vr[dp][3] &= m23;
             }
         }
 #pragma unroll
@@ -125,7 +151,7 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(AttnParams p, int S) 
             floatx4 z = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < D / 32; ++ks)
-                z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.k[ks]), qb[x][ks], z, 0, 0, 0);
+                z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[ks]), qb[x][ks], z, 0, 0, 0);
             if ((pg + 1) * kPage > n_lo) {  // the diagonal crosses this page: mask per column
                 const int key0 = pg * kPage + 4 * kb;
 #pragma unroll
@@ -154,8 +180,8 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(AttnParams p, int S) 
             l[x] += (p0 + p1) + (p2 + p3);
 #pragma unroll
             for (int dp = 0; dp < D / 32; ++dp) {
-                u32x2 lo = {r.v[dp][0], r.v[dp][1]};
-                u32x2 hi = {r.v[dp][2], r.v[dp][3]};
+                u32x2 lo = {vr[dp][0], vr[dp][1]};
+                u32x2 hi = {vr[dp][2], vr[dp][3]};
                 acc[x][2 * dp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, lo), pb,
                                                                            acc[x][2 * dp], 0, 0, 0);
                 acc[x][2 * dp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, hi), pb,
@@ -164,35 +190,25 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(AttnParams p, int S) 
         }
     };
 
-    // pages 0 .. n_pages-1 in order, the next page's loads in flight while the current one is used
-    if (n_pages > 0) {
-        PageRegs<D> ra, rb;
-        int pg = 0;
-        load_page<D, PAGED>(ra, p.slot, b, g, 0, lane_off, p.dev_err);
-        for (;;) {
-            if (pg + 1 < n_pages) {
-                load_page<D, PAGED>(rb, p.slot, b, g, pg + 1, lane_off, p.dev_err);
-                consume(ra, pg);
-            } else {
-                consume(ra, pg);
-                break;
-            }
-            ++pg;
-            if (pg + 1 < n_pages) {
-                load_page<D, PAGED>(ra, p.slot, b, g, pg + 1, lane_off, p.dev_err);
-                consume(rb, pg);
-            } else {
-                consume(rb, pg);
-                break;
-            }
-            ++pg;
+    // Tile t is consumed while tile t+1 is on its way.  One barrier per tile: past it, every wave's share of
+    // tile t has landed (each waited for its own loads first) and every wave has finished reading tile t-1, whose
+    // buffer the loads of tile t+1 then overwrite.
+    issue_tile(0);
+    for (int t = 0; t < n_tiles; ++t) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (t + 1 < n_tiles) issue_tile(t + 1);
+#pragma unroll
+        for (int j = 0; j < NPG; ++j) {
+            const int pg = t * NPG + j;
+            if (pg < n_pages) consume_page(&lds[t & 1][j * kPair], pg);
         }
     }
+    if (!active) return;
 
 #pragma unroll
     for (int x = 0; x < QB; ++x) {
-        float L = l[x];
-        L = column_sum4(L);
+        const float L = column_sum4(l[x]);
         const int i = i_lo + 16 * x + c;
         if (i >= S) continue;
         const float inv = (i < len && L > 0.f) ? 1.f / L : 0.f;  // rows past the prompt, and a token that sees
@@ -207,14 +223,16 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(AttnParams p, int S) 
     }
 }
 
-template <int D, int QB>
+template <int D, int QB, int NPG>
 hipError_t launch_qb(const AttnParams &p, int S, hipStream_t s) {
     const int rows_per_group = 4 * 16 * QB;
-    dim3 grid((S + rows_per_group - 1) / rows_per_group, p.Hq, p.B), block(256);
+    const int64_t total = (int64_t)((S + rows_per_group - 1) / rows_per_group) * p.Hq * p.B;
+    if (total > (int64_t)1 << 30) return hipErrorInvalidValue;
+    dim3 grid((unsigned)((total + 7) / 8 * 8)), block(256);  // one task per workgroup, padded to the 8 XCDs
     if (p.slot.table)
-        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, true>), grid, block, 0, s, p, S);
+        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, NPG, true>), grid, block, 0, s, p, S);
     else
-        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, false>), grid, block, 0, s, p, S);
+        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, NPG, false>), grid, block, 0, s, p, S);
     return hipGetLastError();
 }
 
@@ -222,9 +240,9 @@ hipError_t launch_qb(const AttnParams &p, int S, hipStream_t s) {
 
 // p: seq_lens = prompt lengths, max_n = min(S, capacity), self_visible, scale; no splits.
 hipError_t launch_prefill_bf16(const AttnParams &p, int S, int D, int qb, hipStream_t s) {
-    if (qb == 0) qb = D == 128 ? 2 : 4;  // what fits the register file without spilling
-    if (D == 128) return qb == 2 ? launch_qb<128, 2>(p, S, s) : launch_qb<128, 4>(p, S, s);
-    return qb == 2 ? launch_qb<64, 2>(p, S, s) : launch_qb<64, 4>(p, S, s);
+    if (qb == 0) qb = D == 128 ? 2 : 4;
+    if (D == 128) return qb == 2 ? launch_qb<128, 2, 2>(p, S, s) : launch_qb<128, 4, 2>(p, S, s);
+    return qb == 2 ? launch_qb<64, 2, 4>(p, S, s) : launch_qb<64, 4, 4>(p, S, s);
 }
 
 }  // namespace lckv
