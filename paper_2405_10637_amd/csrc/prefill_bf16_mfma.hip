@@ -7,7 +7,7 @@
 // Same matrix tiles and page layout as the decode kernel, but the 16 columns of a tile are 16 consecutive query
 // positions of one head instead of the heads of a group, and each column has its own number of visible keys:
 //   S^T[key][pos] = K_page . Q^T       (v_mfma_f32_16x16x32_bf16)
-//   O^T[d][pos]  += V_page^T . P^T     (v_mfma_f32_16x16x16_bf16)
+//   O^T[d][pos]  += V_pages^T . P^T    (v_mfma_f32_16x16x32_bf16 over two pages = 32 keys at a time)
 // A workgroup of 4 waves owns 4 * QB blocks of 16 positions of one head (QB per wave) and walks the key pages
 // 0 .. diagonal once.  Pages are brought into LDS by direct global-to-LDS loads (global_load_lds_dwordx4; the
 // cache stores pages in operand order, so the LDS image needs no rearrangement and every wave reads its operands
@@ -24,12 +24,15 @@ typedef __attribute__((address_space(1))) const void *GlobalPtr;
 typedef __attribute__((address_space(3))) void *LdsPtr;
 
 template <int D, int QB, int NPG, bool PAGED>
-__global__ __launch_bounds__(256) void prefill_bf16_kernel(AttnParams p, int S) {
+__global__ __launch_bounds__(256, (D * QB > 256 ? 1 : 2)) void prefill_bf16_kernel(AttnParams p, int S) {
+    // (two workgroups per compute unit = at most 256 vector registers, except for the 128-channel, 4-block shape,
+    //  whose accumulators alone need 128 of them)
     constexpr int kRows = 16 * QB;                 // query positions per wave
     constexpr int kPair = 2 * kPage * D * 2;       // bytes of a K page + V page
     constexpr int kLoadsPerPage = kPair / 1024;    // 1 KiB per wave-wide load
     constexpr int kLoadsPerWave = NPG * kLoadsPerPage / 4;
     static_assert(NPG * kLoadsPerPage % 4 == 0, "a tile's loads must divide among the four waves");
+    static_assert(NPG % 2 == 0, "pages are consumed in pairs");
     __shared__ __attribute__((aligned(16))) char lds[2][NPG * kPair];
 
     // Which (sequence, head, row chunk) this workgroup takes.  Workgroups are handed to the 8 XCDs round-robin
@@ -125,40 +128,62 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(AttnParams p, int S) 
         }
     };
 
-    auto consume_page = [&](const char *page, int pg) {
-        u32x4 kr[D / 32], vr[D / 32];
+    // Two consecutive pages (32 keys) at a time: one softmax update per 32 keys, and the P.V product runs on the
+    // full-rate 16x16x32 instruction - its 8 keys per lane are this lane's 4 keys of the first page and its 4
+    // keys of the second, which is how the two score tiles and the two V operands already sit in registers.
+    // `second` (wave-uniform) is false when the pair's second page lies above this wave's diagonal.
+    // In three phases (scores of all QB blocks, softmax, P.V of all blocks) so that the K operands and the V
+    // operands are not live in registers at the same time.
+    auto consume_pair = [&](const char *page0, int pg, bool second) {
+        const char *page1 = page0 + kPair;
+        floatx4 z0[QB], z1[QB];
+        bool live[QB];  // wave-uniform: the block sees at least one key of the pair
+        {
+            u32x4 kr[D / 32];
 #pragma unroll
-        for (int ks = 0; ks < D / 32; ++ks) kr[ks] = *(const u32x4 *)(page + ks * 1024 + lane_off);
+            for (int ks = 0; ks < D / 32; ++ks) kr[ks] = *(const u32x4 *)(page0 + ks * 1024 + lane_off);
 #pragma unroll
-        for (int dp = 0; dp < D / 32; ++dp) vr[dp] = *(const u32x4 *)(page + kPair / 2 + dp * 1024 + lane_off);
-        if ((pg + 1) * kPage > len) {  // last, partly filled page of the prompt: clear stale values (0 * NaN)
-            int nv = len - (pg * kPage + 4 * kb);
-            uint32_t m01 = nv >= 2 ? 0xffffffffu : (nv == 1 ? 0x0000ffffu : 0u);
-            uint32_t m23 = nv >= 4 ? 0xffffffffu : (nv == 3 ? 0x0000ffffu : 0u);
+            for (int x = 0; x < QB; ++x) {
+                const int n_hi = min(i_lo + 16 * x + 15 + self, len);  // keys the last column of the block sees
+                live[x] = pg * kPage < n_hi;
+                z0[x] = floatx4{0.f, 0.f, 0.f, 0.f};
+                z1[x] = floatx4{kNegInf, kNegInf, kNegInf, kNegInf};
+                if (!live[x]) continue;
 #pragma unroll
-            for (int dp = 0; dp < D / 32; ++dp) {
-                vr[dp][0] &= m01;
-                vr[dp][1] &= m23;
-                vr[dp][2] &= m01;
-                vr[dp][3] &= m23;
+                for (int ks = 0; ks < D / 32; ++ks)
+                    z0[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[ks]), qb[x][ks],
+                                                                    z0[x], 0, 0, 0);
+            }
+            if (second) {
+#pragma unroll
+                for (int ks = 0; ks < D / 32; ++ks) kr[ks] = *(const u32x4 *)(page1 + ks * 1024 + lane_off);
+#pragma unroll
+                for (int x = 0; x < QB; ++x) {
+                    const int n_hi = min(i_lo + 16 * x + 15 + self, len);
+                    if ((pg + 1) * kPage >= n_hi) continue;  // the second page lies above this block's diagonal
+                    z1[x] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < D / 32; ++ks)
+                        z1[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[ks]), qb[x][ks],
+                                                                        z1[x], 0, 0, 0);
+                }
             }
         }
+        bf16x8 pb[QB];
 #pragma unroll
         for (int x = 0; x < QB; ++x) {
-            const int n_lo = min(i_lo + 16 * x + self, len);       // keys the first column of the block sees
-            const int n_hi = min(i_lo + 16 * x + 15 + self, len);  // ... and the last
-            if (pg * kPage >= n_hi) continue;                      // the whole page lies above the diagonal
-            floatx4 z = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < D / 32; ++ks)
-                z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[ks]), qb[x][ks], z, 0, 0, 0);
-            if ((pg + 1) * kPage > n_lo) {  // the diagonal crosses this page: mask per column
+            if (!live[x]) continue;
+            const int n_lo = min(i_lo + 16 * x + self, len);  // keys the first column of the block sees
+            if ((pg + 2) * kPage > n_lo) {                    // the diagonal crosses this pair: mask per column
                 const int key0 = pg * kPage + 4 * kb;
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (key0 + e >= n_col[x]) z[e] = kNegInf;
+                for (int e = 0; e < 4; ++e) {
+                    if (key0 + e >= n_col[x]) z0[x][e] = kNegInf;
+                    if (key0 + kPage + e >= n_col[x]) z1[x][e] = kNegInf;
+                }
             }
-            float smax = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+            float smax = fmaxf(fmaxf(fmaxf(z0[x][0], z0[x][1]), fmaxf(z0[x][2], z0[x][3])),
+                               fmaxf(fmaxf(z1[x][0], z1[x][1]), fmaxf(z1[x][2], z1[x][3])));
             smax = column_max4(smax);
             const float m_new = fmaxf(m[x], smax);
             const float m_use = m_new == kNegInf ? 0.f : m_new;  // a column that has seen no key yet
@@ -166,26 +191,44 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(AttnParams p, int S) 
             const float alpha = __builtin_amdgcn_exp2f((m[x] - m_use) * cs);
             const bool grew = __builtin_amdgcn_ballot_w64(m_new > m[x]) != 0;
             m[x] = m_new;
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(z[0], cs, -mb));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(z[1], cs, -mb));
-            const float p2 = __builtin_amdgcn_exp2f(__builtin_fmaf(z[2], cs, -mb));
-            const float p3 = __builtin_amdgcn_exp2f(__builtin_fmaf(z[3], cs, -mb));
-            u32x2 pk = {pack_bf16(p0, p1), pack_bf16(p2, p3)};
-            const shortx4 pb = __builtin_bit_cast(shortx4, pk);
+            float pr[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                pr[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(z0[x][e], cs, -mb));
+                pr[4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(z1[x][e], cs, -mb));
+            }
+            const u32x4 pk = {pack_bf16(pr[0], pr[1]), pack_bf16(pr[2], pr[3]), pack_bf16(pr[4], pr[5]),
+                              pack_bf16(pr[6], pr[7])};
+            pb[x] = __builtin_bit_cast(bf16x8, pk);
             if (grew) {
                 l[x] *= alpha;
 #pragma unroll
                 for (int j = 0; j < D / 16; ++j) acc[x][j] *= alpha;
             }
-            l[x] += (p0 + p1) + (p2 + p3);
+            l[x] += ((pr[0] + pr[1]) + (pr[2] + pr[3])) + ((pr[4] + pr[5]) + (pr[6] + pr[7]));
+        }
+        uint32_t a01 = 0xffffffffu, a23 = 0xffffffffu, b01 = 0xffffffffu, b23 = 0xffffffffu;
+        if ((pg + 2) * kPage > len) {  // the prompt ends inside this pair: clear stale values (0 * NaN)
+            const int nv0 = len - (pg * kPage + 4 * kb), nv1 = nv0 - kPage;
+            a01 = nv0 >= 2 ? 0xffffffffu : (nv0 == 1 ? 0x0000ffffu : 0u);
+            a23 = nv0 >= 4 ? 0xffffffffu : (nv0 == 3 ? 0x0000ffffu : 0u);
+            b01 = nv1 >= 2 ? 0xffffffffu : (nv1 == 1 ? 0x0000ffffu : 0u);
+            b23 = nv1 >= 4 ? 0xffffffffu : (nv1 == 3 ? 0x0000ffffu : 0u);
+        }
+        if (!second) b01 = b23 = 0u;  // that LDS page holds nothing of this wave's
 #pragma unroll
-            for (int dp = 0; dp < D / 32; ++dp) {
-                u32x2 lo = {vr[dp][0], vr[dp][1]};
-                u32x2 hi = {vr[dp][2], vr[dp][3]};
-                acc[x][2 * dp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, lo), pb,
-                                                                           acc[x][2 * dp], 0, 0, 0);
-                acc[x][2 * dp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, hi), pb,
-                                                                               acc[x][2 * dp + 1], 0, 0, 0);
+        for (int dp = 0; dp < D / 32; ++dp) {
+            const u32x4 v0 = *(const u32x4 *)(page0 + kPair / 2 + dp * 1024 + lane_off);
+            const u32x4 v1 = *(const u32x4 *)(page1 + kPair / 2 + dp * 1024 + lane_off);
+            const u32x4 lo = {v0[0] & a01, v0[1] & a23, v1[0] & b01, v1[1] & b23};  // channel block 2dp, 8 keys
+            const u32x4 hi = {v0[2] & a01, v0[3] & a23, v1[2] & b01, v1[3] & b23};  // channel block 2dp + 1
+#pragma unroll
+            for (int x = 0; x < QB; ++x) {
+                if (!live[x]) continue;
+                acc[x][2 * dp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lo), pb[x],
+                                                                         acc[x][2 * dp], 0, 0, 0);
+                acc[x][2 * dp + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, hi), pb[x],
+                                                                             acc[x][2 * dp + 1], 0, 0, 0);
             }
         }
     };
@@ -199,9 +242,9 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(AttnParams p, int S) 
         __syncthreads();
         if (t + 1 < n_tiles) issue_tile(t + 1);
 #pragma unroll
-        for (int j = 0; j < NPG; ++j) {
+        for (int j = 0; j < NPG; j += 2) {
             const int pg = t * NPG + j;
-            if (pg < n_pages) consume_page(&lds[t & 1][j * kPair], pg);
+            if (pg < n_pages) consume_pair(&lds[t & 1][j * kPair], pg, pg + 1 < n_pages);
         }
     }
     if (!active) return;
