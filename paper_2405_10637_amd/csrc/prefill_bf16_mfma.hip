@@ -11,7 +11,7 @@
 // A workgroup of 4 waves owns 4 * QB blocks of 16 positions of one head (QB per wave) and walks the key pages
 // 0 .. diagonal once.  Pages are brought into LDS by direct global-to-LDS loads (global_load_lds_dwordx4; the
 // cache stores pages in operand order, so the LDS image needs no rearrangement and every wave reads its operands
-// with conflict-free ds_read_b128), two tiles of NPG pages in flight, and every page feeds all 64 * QB queries of
+// with conflict-free ds_read_b128), ST tiles of NPG pages in flight, and every page feeds all 64 * QB queries of
 // the workgroup.  No merge between waves.  Compute-bound; the K/V of a head (S * D * 4 bytes) stay in the L2 of
 // the XCD that runs all row chunks of that head.
 #include "bf16_mfma_common.h"
@@ -20,20 +20,24 @@ namespace lckv {
 
 namespace {
 
-typedef __attribute__((address_space(1))) const void *GlobalPtr;
 typedef __attribute__((address_space(3))) void *LdsPtr;
+typedef __attribute__((address_space(4))) const int32_t *ConstTablePtr;
 
-template <int D, int QB, int NPG, bool PAGED>
-__global__ __launch_bounds__(256, (D * QB > 256 ? 1 : 2)) void prefill_bf16_kernel(AttnParams p, int S) {
-    // (two workgroups per compute unit = at most 256 vector registers, except for the 128-channel, 4-block shape,
-    //  whose accumulators alone need 128 of them)
+template <int D, int QB, int NPG, int ST, bool PAGED>
+__global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void prefill_bf16_kernel(AttnParams p, int S) {
+    // (waves per SIMD the register budget is cut for: within a wave the score products, the softmax and the P.V
+    //  products run one after the other, so it is the other waves of the SIMD that keep the matrix core busy
+    //  meanwhile - 3 waves at 2 query blocks per wave measured faster than 2 waves with more registers each; the
+    //  128-channel, 4-block shape needs 128 registers for its accumulators alone)
     constexpr int kRows = 16 * QB;                 // query positions per wave
     constexpr int kPair = 2 * kPage * D * 2;       // bytes of a K page + V page
     constexpr int kLoadsPerPage = kPair / 1024;    // 1 KiB per wave-wide load
     constexpr int kLoadsPerWave = NPG * kLoadsPerPage / 4;
     static_assert(NPG * kLoadsPerPage % 4 == 0, "a tile's loads must divide among the four waves");
     static_assert(NPG % 2 == 0, "pages are consumed in pairs");
-    __shared__ __attribute__((aligned(16))) char lds[2][NPG * kPair];
+    constexpr float kLazy = 8.f;
+    static_assert(ST >= 2 && ST <= 4, "tiles in flight");
+    __shared__ __attribute__((aligned(16))) char lds[ST][NPG * kPair];
 
     // Which (sequence, head, row chunk) this workgroup takes.  Workgroups are handed to the 8 XCDs round-robin
     // by their launch index, and every XCD has an L2 of its own: the launch index is unfolded so that each XCD
@@ -72,22 +76,10 @@ __global__ __launch_bounds__(256, (D * QB > 256 ? 1 : 2)) void prefill_bf16_kern
     }
     if (i_wg >= len) return;  // uniform over the workgroup: nothing to attend
 
-    // Q^T operands and the number of keys each column sees
-    bf16x8 qb[QB][D / 32];
-    int n_col[QB];
+    bf16x8 qb[QB][D / 32];  // Q^T operands (loaded below, behind the first tiles' loads)
+    int n_col[QB];          // the number of keys each column sees
 #pragma unroll
-    for (int x = 0; x < QB; ++x) {
-        const int i = i_lo + 16 * x + c;
-        n_col[x] = min(i + self, len);
-        const char *qp = (const char *)p.q + ((((int64_t)b * S + i) * p.Hq + h) * D + kb * 8) * 2;
-#pragma unroll
-        for (int ks = 0; ks < D / 32; ++ks) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (active && i < S) v = *(const u32x4 *)(qp + ks * 64);
-            qb[x][ks] = __builtin_bit_cast(bf16x8, v);
-        }
-    }
-
+    for (int x = 0; x < QB; ++x) n_col[x] = min(i_lo + 16 * x + c + self, len);
     floatx4 acc[QB][D / 16];
     float m[QB], l[QB];
 #pragma unroll
@@ -113,7 +105,9 @@ __global__ __launch_bounds__(256, (D * QB > 256 ? 1 : 2)) void prefill_bf16_kern
             if (pg >= n_pages_wg) pg = n_pages_wg - 1;  // past the end: any mapped page, it is not used
             int64_t idx;
             if (PAGED) {
-                int32_t blk = p.slot.table[(int64_t)b * p.slot.max_blocks + pg];
+                // read through the constant address space: a scalar load, which does not queue behind the tile
+                // loads in flight as a vector load would (the table is not written while the kernel runs)
+                int32_t blk = ((ConstTablePtr)p.slot.table)[(int64_t)b * p.slot.max_blocks + pg];
                 if (blk < 0 || (int64_t)blk >= p.slot.num_blocks) {
                     if (lane == 0) atomicOr(p.dev_err, LCKV_DEV_ERR_BLOCK);
                     blk = 0;  // read something that exists; this sequence's result is undefined, the error is raised
@@ -123,8 +117,13 @@ __global__ __launch_bounds__(256, (D * QB > 256 ? 1 : 2)) void prefill_bf16_kern
                 idx = ((int64_t)b * p.slot.Hkv + g) * p.slot.pages_per_seq + pg;
             }
             const char *src = p.slot.base + idx * kPair + (piece % kLoadsPerPage) * 1024 + lane_off;
-            // lane l's 16 bytes land at the LDS address + 16 * l
-            __builtin_amdgcn_global_load_lds((GlobalPtr)src, (LdsPtr)(&lds[t & 1][piece * 1024]), 16, 0, 0);
+            // global_load_lds_dwordx4: lane l's 16 bytes land at LDS address M0 + 16 * l.  Issued as assembly, not
+            // through the compiler's builtin: the compiler cannot tell which LDS reads such a load may alias and
+            // makes every LDS read after one wait for ALL loads in flight, which forfeits the prefetch.  The
+            // waits are placed by hand below.
+            const uint32_t dst = (uint32_t)(uintptr_t)(LdsPtr)(&lds[t % ST][piece * 1024]);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src)
+                         : "memory", "m0");
         }
     };
 
@@ -185,12 +184,19 @@ __global__ __launch_bounds__(256, (D * QB > 256 ? 1 : 2)) void prefill_bf16_kern
             float smax = fmaxf(fmaxf(fmaxf(z0[x][0], z0[x][1]), fmaxf(z0[x][2], z0[x][3])),
                                fmaxf(fmaxf(z1[x][0], z1[x][1]), fmaxf(z1[x][2], z1[x][3])));
             smax = column_max4(smax);
-            const float m_new = fmaxf(m[x], smax);
-            const float m_use = m_new == kNegInf ? 0.f : m_new;  // a column that has seen no key yet
-            const float mb = m_use * cs;
-            const float alpha = __builtin_amdgcn_exp2f((m[x] - m_use) * cs);
-            const bool grew = __builtin_amdgcn_ballot_w64(m_new > m[x]) != 0;
-            m[x] = m_new;
+            // The running reference m[x] follows the true maximum lazily: the accumulators are rescaled only when
+            // some column's maximum has outgrown its reference by more than 2^kLazy (or has no reference yet), so
+            // the weights stay <= 2^kLazy - harmless in fp32 sums and at bf16's relative precision - and the result
+            // O / l is the same quotient.  (Both -inf: the comparison is false, nothing has been seen.)
+            if (__builtin_amdgcn_ballot_w64((smax - m[x]) * cs > kLazy) != 0) {
+                const float m_new = fmaxf(m[x], smax);
+                const float alpha = __builtin_amdgcn_exp2f((m[x] - (m_new == kNegInf ? 0.f : m_new)) * cs);
+                m[x] = m_new;
+                l[x] *= alpha;
+#pragma unroll
+                for (int j = 0; j < D / 16; ++j) acc[x][j] *= alpha;
+            }
+            const float mb = (m[x] == kNegInf ? 0.f : m[x]) * cs;
             float pr[8];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -200,11 +206,6 @@ __global__ __launch_bounds__(256, (D * QB > 256 ? 1 : 2)) void prefill_bf16_kern
             const u32x4 pk = {pack_bf16(pr[0], pr[1]), pack_bf16(pr[2], pr[3]), pack_bf16(pr[4], pr[5]),
                               pack_bf16(pr[6], pr[7])};
             pb[x] = __builtin_bit_cast(bf16x8, pk);
-            if (grew) {
-                l[x] *= alpha;
-#pragma unroll
-                for (int j = 0; j < D / 16; ++j) acc[x][j] *= alpha;
-            }
             l[x] += ((pr[0] + pr[1]) + (pr[2] + pr[3])) + ((pr[4] + pr[5]) + (pr[6] + pr[7]));
         }
         uint32_t a01 = 0xffffffffu, a23 = 0xffffffffu, b01 = 0xffffffffu, b23 = 0xffffffffu;
@@ -233,18 +234,44 @@ __global__ __launch_bounds__(256, (D * QB > 256 ? 1 : 2)) void prefill_bf16_kern
         }
     };
 
-    // Tile t is consumed while tile t+1 is on its way.  One barrier per tile: past it, every wave's share of
-    // tile t has landed (each waited for its own loads first) and every wave has finished reading tile t-1, whose
-    // buffer the loads of tile t+1 then overwrite.
-    issue_tile(0);
+    // Tile t is consumed while tiles t+1 .. t+ST-1 are on their way (a page that misses the L2 takes longer to
+    // arrive than a tile takes to consume).  One barrier per tile: past it, every wave's share of tile t has
+    // landed (each waited for its own loads first: they complete in order, so "at most as many outstanding as the
+    // later tiles have" means tile t is there) and every wave has finished reading tile t-1, whose buffer the
+    // loads of tile t+ST-1 then overwrite.
+    for (int t = 0; t < ST - 1 && t < n_tiles; ++t) issue_tile(t);
+    // Q^T operands, loaded behind the first tiles and waited for here, before the loop: a wait for them inside
+    // the loop would be a wait for all loads in flight.
+#pragma unroll
+    for (int x = 0; x < QB; ++x) {
+        const int i = i_lo + 16 * x + c;
+        const char *qp = (const char *)p.q + ((((int64_t)b * S + i) * p.Hq + h) * D + kb * 8) * 2;
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ++ks) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (active && i < S) v = *(const u32x4 *)(qp + ks * 64);
+            qb[x][ks] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+#pragma unroll
+    for (int x = 0; x < QB; ++x)
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ++ks) asm volatile("" ::"v"(qb[x][ks]));  // a use: the compiler waits here
     for (int t = 0; t < n_tiles; ++t) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (t + 1 < n_tiles) issue_tile(t + 1);
+        const int later = min(ST - 2, n_tiles - 1 - t);  // tiles issued after tile t
+        if (later <= 0)
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (later == 1)
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerWave) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kLoadsPerWave) : "memory");
+        // the bare barrier instruction: __syncthreads() comes with a fence that waits for ALL outstanding loads
+        asm volatile("s_barrier" ::: "memory");
+        if (t + ST - 1 < n_tiles) issue_tile(t + ST - 1);
 #pragma unroll
         for (int j = 0; j < NPG; j += 2) {
             const int pg = t * NPG + j;
-            if (pg < n_pages) consume_pair(&lds[t & 1][j * kPair], pg, pg + 1 < n_pages);
+            if (pg < n_pages) consume_pair(&lds[t % ST][j * kPair], pg, pg + 1 < n_pages);
         }
     }
     if (!active) return;
@@ -266,16 +293,16 @@ __global__ __launch_bounds__(256, (D * QB > 256 ? 1 : 2)) void prefill_bf16_kern
     }
 }
 
-template <int D, int QB, int NPG>
+template <int D, int QB, int NPG, int ST = 3>
 hipError_t launch_qb(const AttnParams &p, int S, hipStream_t s) {
     const int rows_per_group = 4 * 16 * QB;
     const int64_t total = (int64_t)((S + rows_per_group - 1) / rows_per_group) * p.Hq * p.B;
     if (total > (int64_t)1 << 30) return hipErrorInvalidValue;
     dim3 grid((unsigned)((total + 7) / 8 * 8)), block(256);  // one task per workgroup, padded to the 8 XCDs
     if (p.slot.table)
-        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, NPG, true>), grid, block, 0, s, p, S);
+        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, NPG, ST, true>), grid, block, 0, s, p, S);
     else
-        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, NPG, false>), grid, block, 0, s, p, S);
+        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, NPG, ST, false>), grid, block, 0, s, p, S);
     return hipGetLastError();
 }
 

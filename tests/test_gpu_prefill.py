@@ -53,10 +53,11 @@ def test_prefill_bf16_mha_d128_ragged():
     run_prefill(wl, 300, [300, 0, 1, 17, 150])
 
 
-def test_prefill_bf16_mha_d128_four_blocks_per_wave():
-    wl = synth.Workload("p-mha128-qb4", "bf16", L=2, w=1, Hq=2, Hkv=2, D=128, B=2, T=280, sigma=1.0, seed=42,
-                        warm=(0,))
-    run_prefill(wl, 280, [280, 33], tile=4)
+@pytest.mark.parametrize("tile", [2, 4])
+def test_prefill_bf16_mha_d128_blocks_per_wave(tile):
+    wl = synth.Workload("p-mha128-qb%d" % tile, "bf16", L=2, w=1, Hq=2, Hkv=2, D=128, B=2, T=280, sigma=1.0,
+                        seed=42, warm=(0,))
+    run_prefill(wl, 280, [280, 33], tile=tile)
 
 
 @pytest.mark.parametrize("tile", [2, 4])
