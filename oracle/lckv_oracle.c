@@ -21,6 +21,9 @@
  * The sink + window cache policy of Section 3.3 (StreamingLLM integration) is
  * an option of the step; it is written as a selection of logical positions
  * from the full history, not as a ring buffer.
+ * lckv_oracle_project is the q / k / v projection with the rotary position
+ * embedding, the step either side of the attention (which layers have K/V
+ * projections at all is the pairing table's producer column).
  * "Parity unpinned": which layer owns the shared cache when the topmost
  * layers are warmup layers (pairing rule 1 vs rule 2 below) is not decided by
  * the paper; both are implemented, rule 1 is the default.
@@ -328,6 +331,55 @@ int lckv_oracle_prefill_attention(int Hq, int Hkv, int D, int B, int64_t S,
         }
     }
     return used;
+}
+
+/*
+ * The projections either side of the attention.  Section 2.1: a layer whose
+ * K/V nobody reads does not compute them and has no W_K, W_V at all - only the
+ * layers that PRODUCE a cache slot (warmup layers and the one condensed layer
+ * that owns the shared cache, see lckv_oracle_pairing) map the hidden state to
+ * keys and values; every layer maps it to queries.  This function is the map
+ * itself, for one weight matrix:
+ *     y[b][n] = sum_c x[b][c] * W[n][c]            (W is [N][hidden], N = n_heads*D)
+ * followed, when pos != NULL (queries and keys; never values), by the rotary
+ * position embedding in the convention of the Llama models the paper trains
+ * (the paper itself does not restate it): within each head, channel i < D/2 is
+ * paired with channel i + D/2 and the pair is rotated by the angle
+ *     pos[b] * base^(-2i/D).
+ *   x [B][hidden] float, W [N][hidden] float, pos [B] or NULL, out [B][N] double
+ * Returns 0, or -1 on a bad argument.
+ */
+int lckv_oracle_project(int B, int hidden, int n_heads, int D, const float *x,
+                        const float *W, const int64_t *pos, double rope_base,
+                        double *out)
+{
+    if (B < 0 || hidden < 1 || n_heads < 1 || D < 2 || (D & 1) || !x || !W || !out)
+        return -1;
+    if (pos && !(rope_base > 0.0))
+        return -1;
+    const int64_t N = (int64_t)n_heads * D;
+    for (int b = 0; b < B; ++b) {
+        double *y = out + (int64_t)b * N;
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int c = 0; c < hidden; ++c)
+                acc += (double)x[(int64_t)b * hidden + c] * (double)W[n * hidden + c];
+            y[n] = acc;
+        }
+        if (!pos)
+            continue;
+        for (int h = 0; h < n_heads; ++h) {
+            double *v = y + (int64_t)h * D;
+            for (int i = 0; i < D / 2; ++i) {
+                const double angle = (double)pos[b] * pow(rope_base, -2.0 * i / D);
+                const double c = cos(angle), s = sin(angle);
+                const double lo = v[i], hi = v[i + D / 2];
+                v[i] = lo * c - hi * s;
+                v[i + D / 2] = hi * c + lo * s;
+            }
+        }
+    }
+    return 0;
 }
 
 int lckv_oracle_max_threads(void)

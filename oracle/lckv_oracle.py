@@ -74,6 +74,8 @@ def _load():
         lib.lckv_oracle_prefill_attention.argtypes = [ctypes.c_int] * 4 + [
             ctypes.c_int64, ctypes.c_int64, f32p, f32p, i32p, ctypes.c_int, ctypes.c_double, f32p, f64p, ctypes.c_int]
         lib.lckv_oracle_prefill_attention.restype = ctypes.c_int
+        lib.lckv_oracle_project.argtypes = [ctypes.c_int] * 4 + [f32p, f32p, i64p, ctypes.c_double, f64p]
+        lib.lckv_oracle_project.restype = ctypes.c_int
         lib.lckv_oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -199,3 +201,24 @@ def prefill_attention(Kc, Vc, lens, q, self_visible: bool, scale: float, threads
     if rc < 0:
         raise ValueError("lckv_oracle_prefill_attention: bad argument")
     return out, int(rc)
+
+
+def project(x, W, n_heads: int, pos=None, rope_base: float = 10000.0):
+    """One projection either side of the attention (Section 2.1): y = x W^T with W [n_heads*D][hidden], then, when
+    `pos` (int [B]) is given, the rotary position embedding per head (queries and keys; never values).
+    Returns float64 [B][n_heads][D]."""
+    x, W = _f32(x), _f32(W)
+    B, hidden = x.shape
+    N = W.shape[0]
+    assert W.shape == (N, hidden) and N % n_heads == 0
+    D = N // n_heads
+    out = np.zeros((B, N), np.float64)
+    if pos is not None:
+        pos = np.ascontiguousarray(pos, dtype=np.int64)
+        assert pos.shape == (B,)
+    rc = _load().lckv_oracle_project(B, hidden, n_heads, D, _p(x, ctypes.c_float), _p(W, ctypes.c_float),
+                                     _p(pos, ctypes.c_int64) if pos is not None else None, float(rope_base),
+                                     _p(out, ctypes.c_double))
+    if rc < 0:
+        raise ValueError("lckv_oracle_project: bad argument")
+    return out.reshape(B, n_heads, D)

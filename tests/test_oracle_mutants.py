@@ -8,6 +8,7 @@ import pytest
 from oracle import lckv_oracle as orc
 import test_oracle_pins as pins
 import test_oracle_prefill_pins as prefill_pins
+import test_oracle_project_pins as project_pins
 
 SRC = os.path.join(os.path.dirname(orc.__file__), "lckv_oracle.c")
 
@@ -39,9 +40,21 @@ MUTANTS = {
     "prefill: warmup layer misses itself": ("int64_t n = i + (self_visible ? 1 : 0);", "int64_t n = i;"),
     "prefill: rows past the prompt computed": ("if (i >= lens[b]) {", "if (0) {"),
     "prefill: gqa heads interleaved": ("(int64_t)(h / G) * D;", "(int64_t)(h % Hkv) * D;"),
+    "project: weight read transposed": ("(double)W[n * hidden + c];", "(double)W[(int64_t)c * N + n];"),
+    "rope: rotates the other way": ("v[i] = lo * c - hi * s;\n                v[i + D / 2] = hi * c + lo * s;",
+                                    "v[i] = lo * c + hi * s;\n                v[i + D / 2] = hi * c - lo * s;"),
+    "rope: second half keeps the wrong sign": ("v[i + D / 2] = hi * c + lo * s;", "v[i + D / 2] = hi * c - lo * s;"),
+    "rope: frequency exponent halved": ("pow(rope_base, -2.0 * i / D)", "pow(rope_base, -1.0 * i / D)"),
+    "rope: position off by one": ("(double)pos[b] * pow(", "(double)(pos[b] + 1) * pow("),
+    "rope: adjacent channels paired": ("const double lo = v[i], hi = v[i + D / 2];\n                v[i] = lo * c - hi * s;"
+                                       "\n                v[i + D / 2] = hi * c + lo * s;",
+                                       "const double lo = v[2 * i], hi = v[2 * i + 1];\n"
+                                       "                v[2 * i] = lo * c - hi * s;\n"
+                                       "                v[2 * i + 1] = hi * c + lo * s;"),
+    "rope: only the first head rotated": ("double *v = y + (int64_t)h * D;", "double *v = y + (int64_t)(h > 0 ? 0 : h) * D;"),
 }
 
-PIN_FUNCS = [getattr(mod, n) for mod in (pins, prefill_pins) for n in dir(mod) if n.startswith("test_")]
+PIN_FUNCS = [getattr(mod, n) for mod in (pins, prefill_pins, project_pins) for n in dir(mod) if n.startswith("test_")]
 
 
 def _run_all_pins():
