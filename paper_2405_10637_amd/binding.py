@@ -26,7 +26,7 @@ LCKV_LOAD_AUTO, LCKV_LOAD_TEMPORAL, LCKV_LOAD_NONTEMPORAL = 0, 1, 2
 EXPORTS = [
     "lckv_cache_bytes", "lckv_plan_max_batch", "lckv_cache_alloc", "lckv_cache_free", "lckv_cache_set_block_table", "lckv_n_slots",
     "lckv_kv_slot", "lckv_slot_producer", "lckv_append_kv", "lckv_decode_attention", "lckv_prefill_attention",
-    "lckv_set_prefill_tile", "lckv_step",
+    "lckv_set_prefill_tile", "lckv_project_qkv", "lckv_project_workspace_bytes", "lckv_step",
     "lckv_workspace_bytes", "lckv_set_split_tokens", "lckv_set_load_policy", "lckv_cache_load_dense", "lckv_cache_read",
     "lckv_last_device_error", "lckv_profile_enable", "lckv_profile_read", "lckv_profile_launch_ms",
     "lckv_hbm_read_probe", "lckv_strerror",
@@ -74,6 +74,8 @@ def lib():
         L.lckv_decode_attention.argtypes = [vp, i32, vp, vp, vp, vp, i32, i32, vp, sz, vp]
         L.lckv_prefill_attention.argtypes = [vp, i32, vp, vp, vp, i32, i32, vp]
         L.lckv_set_prefill_tile.argtypes = [vp, i32]
+        L.lckv_project_qkv.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, i32, ctypes.c_float, vp, sz, vp]
+        L.lckv_project_workspace_bytes.argtypes = [vp, i32, ctypes.POINTER(sz)]
         L.lckv_step.argtypes =[vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
         L.lckv_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
         L.lckv_set_split_tokens.argtypes = [vp, i32]
@@ -207,6 +209,22 @@ def lckv_step(cache: int, q_all, k_new_all, v_new_all, out_all, dev_seq_lens, B:
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lckv_step(cache, _ptr(q_all), _ptr(k_new_all), _ptr(v_new_all), _ptr(out_all), _ptr(dev_seq_lens), B,
                            max_len_hint, _ptr(workspace), workspace_bytes, _stream(stream)), "lckv_step")
+
+
+def lckv_project_workspace_bytes(cache: int, B: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().lckv_project_workspace_bytes(cache, B, ctypes.byref(out)), "lckv_project_workspace_bytes")
+    return out.value
+
+
+def lckv_project_qkv(cache: int, layer: int, x, hidden: int, w_q, w_k, w_v, q_out, dev_seq_lens, B: int,
+                     rope_base: float, workspace, stream=None):
+    _check(lib().lckv_project_qkv(cache, layer, _ptr(x), hidden, _ptr(w_q), _ptr(w_k) if w_k is not None else None,
+                                  _ptr(w_v) if w_v is not None else None, _ptr(q_out), _ptr(dev_seq_lens), B,
+                                  float(rope_base), _ptr(workspace),
+                                  0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                  _stream(stream)),
+           "lckv_project_qkv")
 
 
 def lckv_workspace_bytes(cache: int, B: int, max_len_hint: int) -> int:

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblckv.so")
-SOURCES = ["lckv_api.hip", "attn_bf16_mfma.hip", "prefill_bf16_mfma.hip", "attn_f32_valu.hip", "cache_ops.hip"]
+SOURCES = ["lckv_api.hip", "attn_bf16_mfma.hip", "prefill_bf16_mfma.hip", "project_mfma.hip", "attn_f32_valu.hip", "cache_ops.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

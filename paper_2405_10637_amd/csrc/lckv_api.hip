@@ -454,6 +454,49 @@ int lckv_workspace_bytes(const lckv_cache *c, int32_t B, int32_t max_len_hint, s
     return LCKV_OK;
 }
 
+// Workspace of lckv_project_qkv: fp32 accumulator [B][(Hq + 2 Hkv) D], then the cos/sin table [B][D/2].
+static size_t project_acc_bytes(const lckv_cache *c, int B) {
+    size_t n = (size_t)B * ((size_t)c->cfg.Hq + 2 * (size_t)c->cfg.Hkv) * c->cfg.D * sizeof(float);
+    return (n + 255) / 256 * 256;
+}
+
+int lckv_project_workspace_bytes(const lckv_cache *c, int32_t B, size_t *bytes) {
+    if (!valid(c) || !bytes) return LCKV_ERR_NULL;
+    if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
+    size_t rope = (size_t)B * (c->cfg.D / 2) * sizeof(float2);
+    *bytes = project_acc_bytes(c, B) + (rope + 255) / 256 * 256;
+    return LCKV_OK;
+}
+
+int lckv_project_qkv(lckv_cache *c, int32_t layer, const void *x, int32_t hidden, const void *w_q, const void *w_k,
+                     const void *w_v, void *q_out, const int32_t *dev_seq_lens, int32_t B, float rope_base,
+                     void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!valid(c) || !x || !w_q || !q_out || !dev_seq_lens) return LCKV_ERR_NULL;
+    if (layer < 0 || layer >= c->cfg.L) return LCKV_ERR_LAYER;
+    int slot = -1;
+    for (int s = 0; s < c->n_slots; ++s)
+        if (c->producer[s] == layer) slot = s;
+    if (slot < 0 && (w_k || w_v)) return LCKV_ERR_NOT_PRODUCER;
+    if (slot >= 0 && (!w_k || !w_v)) return LCKV_ERR_NULL;
+    if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
+    if (hidden < 1 || (int64_t)hidden * B > ((int64_t)1 << 40)) return LCKV_ERR_CONFIG;
+    if (c->cfg.dtype == LCKV_BF16 && hidden % 256 != 0) return LCKV_ERR_CONFIG;
+    if (slot >= 0 && c->cfg.window_tokens > 0 && !c->self_visible[layer]) return LCKV_ERR_CONFIG;
+    if (slot >= 0 && c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
+    if (!aligned(x, 16) || !aligned(w_q, 16) || !aligned(q_out, 16) || !aligned(dev_seq_lens, 4) ||
+        (w_k && !aligned(w_k, 16)) || (w_v && !aligned(w_v, 16)))
+        return LCKV_ERR_ALIGN;
+    size_t need = 0;
+    lckv_project_workspace_bytes(c, B, &need);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return LCKV_ERR_WORKSPACE;
+    float *acc = (float *)workspace;
+    float2 *rope = (float2 *)((char *)workspace + project_acc_bytes(c, B));
+    hipError_t e = launch_project(x, hidden, w_q, w_k, w_v, q_out, slot_view(c, slot >= 0 ? slot : 0), dev_seq_lens, B,
+                                  c->cfg.Hq, c->cfg.Hkv, c->cfg.D, c->cfg.dtype, rope_base, acc, rope, c->dev_err,
+                                  (hipStream_t)hip_stream);
+    return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
+}
+
 int lckv_set_split_tokens(lckv_cache *c, int32_t tokens) {
     if (!valid(c)) return LCKV_ERR_NULL;
     if (tokens < 0 || tokens % kPage != 0) return LCKV_ERR_CONFIG;

@@ -122,8 +122,12 @@ __global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void pre
             // makes every LDS read after one wait for ALL loads in flight, which forfeits the prefetch.  The
             // waits are placed by hand below.
             const uint32_t dst = (uint32_t)(uintptr_t)(LdsPtr)(&lds[t % ST][piece * 1024]);
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src)
-                         : "memory", "m0");
+            uint32_t m0_saved;  // M0 carries the LDS address; whatever the compiler keeps there is put back
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
+                         "s_mov_b32 m0, %0"
+                         : "=&s"(m0_saved)
+                         : "s"(dst), "v"(src)
+                         : "memory");
         }
     };
 

@@ -1,0 +1,188 @@
+"""GPU parity of lckv_project_qkv (Section 2.1: queries for every layer, keys and values - stored straight into
+the cache - for producing layers only; rotary embedding at position t_b) against the oracle, element by element:
+ragged positions including 0, batches that are not a multiple of 16 and that need two passes, GQA, D = 64 and 128,
+contiguous and paged caches, bf16 and fp32, no rotation; then whole decode steps built from the projection and
+the attention entry points against the same composition of oracle functions."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lckv_oracle as orc
+from paper_2405_10637_amd import binding as lk
+from paper_2405_10637_amd import synth
+
+from gpu_harness import GpuCache, check_close, to_f32_numpy
+
+pytestmark = pytest.mark.gpu
+
+
+def cache_rows_f32(gc, slot, b, pos):
+    """K and V of one position as float32 [Hkv][D]."""
+    k, v = gc.read(slot, b, pos, 1)
+    if gc.wl.dtype == "bf16":
+        k, v = (k.astype(np.uint32) << 16), (v.astype(np.uint32) << 16)
+    return k.view(np.float32)[0], v.view(np.float32)[0]
+
+
+def weights(wl, hidden, layer, producer):
+    n = lambda rows, seed: synth._normal((rows, hidden), 1.0 / np.sqrt(hidden), wl.torch_dtype, seed)
+    wq = n(wl.Hq * wl.D, wl.seed + 100 * layer + 1)
+    if not producer:
+        return wq, None, None
+    return wq, n(wl.Hkv * wl.D, wl.seed + 100 * layer + 2), n(wl.Hkv * wl.D, wl.seed + 100 * layer + 3)
+
+
+def run_project(wl, hidden, lens, T_cap, rope_base=10000.0):
+    print("project case", wl.name, wl.dtype, "H", wl.Hq, wl.Hkv, "D", wl.D, "hidden", hidden, "lens", list(lens)[:8],
+          "paged", wl.paged, "base", rope_base, flush=True)
+    lens = np.asarray(lens, np.int32)
+    with GpuCache(wl, T_cap, lens) as gc:
+        ws = torch.empty(lk.lckv_project_workspace_bytes(gc.h, wl.B), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)                                            # the call must not rely on a cleared workspace
+        producers = {lk.lckv_slot_producer(gc.h, s): s for s in range(gc.n_slots)}
+        pos = lens if rope_base > 0 else None
+        for layer in range(wl.L):
+            x = synth._normal((wl.B, hidden), 1.0, wl.torch_dtype, wl.seed + 7 * layer)
+            wq, wk, wv = weights(wl, hidden, layer, layer in producers)
+            dev = lambda t: None if t is None else t.cuda()
+            before = gc.storage.clone()
+            q_out = torch.full((wl.B, wl.Hq, wl.D), float("nan"), dtype=wl.torch_dtype, device="cuda")
+            lk.lckv_project_qkv(gc.h, layer, x.cuda(), hidden, dev(wq), dev(wk), dev(wv), q_out, gc.lens, wl.B,
+                                rope_base, ws)
+            torch.cuda.synchronize()
+            xf = to_f32_numpy(x)
+            check_close(q_out, orc.project(xf, to_f32_numpy(wq), wl.Hq, pos=pos, rope_base=rope_base), wl.dtype,
+                        "%s layer %d q" % (wl.name, layer))
+            if layer not in producers:
+                assert torch.equal(gc.storage, before), "a layer without K/V projections wrote to the cache"
+                continue
+            slot = producers[layer]
+            want_k = orc.project(xf, to_f32_numpy(wk), wl.Hkv, pos=pos, rope_base=rope_base)
+            want_v = orc.project(xf, to_f32_numpy(wv), wl.Hkv)
+            changed = (gc.storage != before).sum().item()
+            eb = 2 if wl.dtype == "bf16" else 4
+            assert changed <= wl.B * 2 * wl.Hkv * wl.D * eb       # nothing but the new token's K/V bytes
+            for b in range(wl.B):
+                gk, gv = cache_rows_f32(gc, slot, b, int(lens[b]))
+                check_close(torch.from_numpy(gk), want_k[b], wl.dtype, "%s layer %d k[%d]" % (wl.name, layer, b))
+                check_close(torch.from_numpy(gv), want_v[b], wl.dtype, "%s layer %d v[%d]" % (wl.name, layer, b))
+        assert gc.device_error() == 0
+
+
+def test_project_bf16_gqa_d64_contiguous_ragged():
+    wl = synth.Workload("pr-gqa64", "bf16", L=4, w=2, Hq=4, Hkv=2, D=64, B=5, T=48, sigma=1.0, seed=61)
+    run_project(wl, 256, [0, 1, 17, 33, 47], 48)
+
+
+def test_project_bf16_mha_d128_paged_two_passes():
+    wl = synth.Workload("pr-mha128", "bf16", L=3, w=1, Hq=2, Hkv=2, D=128, B=130, T=40, sigma=1.0, seed=62,
+                        paged=True, warm=(0,))
+    lens = (np.arange(130) * 7) % 40
+    run_project(wl, 512, lens, 48)
+
+
+@pytest.mark.parametrize("B", [16, 17, 33, 64])
+def test_project_bf16_batch_blocks(B):
+    wl = synth.Workload("pr-b%d" % B, "bf16", L=2, w=1, Hq=3, Hkv=1, D=64, B=B, T=20, sigma=1.0, seed=63 + B,
+                        warm=(0,))
+    run_project(wl, 256, (np.arange(B) * 3) % 20, 32)
+
+
+def test_project_without_rotation():
+    wl = synth.Workload("pr-norope", "bf16", L=2, w=1, Hq=2, Hkv=2, D=64, B=3, T=20, sigma=1.0, seed=64, warm=(0,))
+    run_project(wl, 256, [3, 0, 19], 32, rope_base=0.0)
+
+
+def test_project_long_positions_keep_their_angle():
+    # position 32767 at the highest frequency is 32767 rad: the angle must be formed in double
+    wl = synth.Workload("pr-long", "bf16", L=2, w=1, Hq=2, Hkv=2, D=128, B=2, T=32768, sigma=1.0, seed=65, warm=(0,))
+    run_project(wl, 256, [32767, 20011], 32768)
+
+
+def test_project_f32():
+    wl = synth.Workload("pr-f32", "f32", L=3, w=1, Hq=4, Hkv=2, D=64, B=4, T=30, sigma=1.0, seed=66, warm=(0,))
+    run_project(wl, 96, [0, 5, 16, 29], 32)
+    wl = synth.Workload("pr-f32p", "f32", L=2, w=1, Hq=2, Hkv=1, D=128, B=3, T=30, sigma=1.0, seed=67, paged=True)
+    run_project(wl, 200, [7, 31, 2], 32)
+
+
+def test_project_argument_errors():
+    wl = synth.Workload("pr-err", "bf16", L=3, w=1, Hq=2, Hkv=2, D=64, B=2, T=32, sigma=1.0, seed=68, warm=(0,))
+    with GpuCache(wl, 32, np.array([3, 4], np.int32)) as gc:
+        L = lk.lib()
+        t = torch.zeros(1 << 16, dtype=torch.bfloat16, device="cuda")
+        ws = torch.empty(lk.lckv_project_workspace_bytes(gc.h, 2), dtype=torch.uint8, device="cuda")
+        p, w, n = t.data_ptr(), ws.data_ptr(), ws.numel()
+        st = torch.cuda.current_stream().cuda_stream or None
+        call = lambda layer, hidden=256, wk=p, wv=p, B=2, wsp=w, wsn=n: L.lckv_project_qkv(
+            gc.h, layer, p, hidden, p, wk, wv, p, gc.lens.data_ptr(), B, 10000.0, wsp, wsn, st)
+        producers = [lk.lckv_slot_producer(gc.h, s) for s in range(gc.n_slots)]
+        other = [l for l in range(wl.L) if l not in producers][0]
+        assert call(other) == lk.LCKV_ERR_NOT_PRODUCER            # such a layer has no W_K, W_V
+        assert call(other, wk=None, wv=None) == lk.LCKV_OK
+        assert call(producers[0], wk=None) == lk.LCKV_ERR_NULL and call(producers[0], wv=None) == lk.LCKV_ERR_NULL
+        assert call(producers[0], hidden=128) == lk.LCKV_ERR_CONFIG
+        assert call(7) == lk.LCKV_ERR_LAYER and call(producers[0], B=3) == lk.LCKV_ERR_BATCH
+        assert call(producers[0], wsn=n - 1) == lk.LCKV_ERR_WORKSPACE and call(producers[0], wsp=None) == \
+            lk.LCKV_ERR_WORKSPACE
+        torch.cuda.synchronize()
+    with GpuCache(wl, 32, np.array([3, 4], np.int32), sink=4, window=28) as gc:
+        shared = [l for l in producers if not lk.lckv_kv_slot(gc.h, l)[1]][0]
+        assert L.lckv_project_qkv(gc.h, shared, p, 256, p, p, p, p, gc.lens.data_ptr(), 2, 10000.0, w, n, st) == \
+            lk.LCKV_ERR_CONFIG
+
+
+def test_decode_steps_from_hidden_states():
+    # Whole steps from the hidden states: per layer, projection (+ fused append) then attention, lengths bumped by
+    # the caller; the same composition of oracle functions beside it.  The hidden state of a layer is a seeded
+    # input (what lies between the layers - output projection, MLP - is outside the path).
+    wl = synth.Workload("pr-steps", "bf16", L=4, w=2, Hq=4, Hkv=2, D=64, B=3, T=40, sigma=1.0, seed=69)
+    hidden, T_cap, steps = 256, 48, 4
+    lens = np.array([5, 0, 30], np.int32)
+    scale = 1.0 / np.sqrt(wl.D)
+    with GpuCache(wl, T_cap, lens) as gc:
+        ns = gc.n_slots
+        K0, V0 = synth.logical_cache(wl, ns, T_cap)
+        for s in range(ns):
+            gc.load_dense(s, K0[s], V0[s])
+        Kf, Vf = to_f32_numpy(K0), to_f32_numpy(V0)                      # oracle's caches [slot][B][T][Hkv][D]
+        producers = {lk.lckv_slot_producer(gc.h, s): s for s in range(ns)}
+        W = [weights(wl, hidden, l, l in producers) for l in range(wl.L)]
+        Wd = [[None if t is None else t.cuda() for t in w] for w in W]
+        ws = torch.empty(lk.lckv_project_workspace_bytes(gc.h, wl.B), dtype=torch.uint8, device="cuda")
+        lens_o = lens.copy()
+        for step in range(steps):
+            hint = int(lens_o.max())
+            aws = gc.workspace(hint)
+            for l in range(wl.L):
+                x = synth._normal((wl.B, hidden), 1.0, torch.bfloat16, 5000 + 10 * step + l)
+                q = torch.empty((wl.B, wl.Hq, wl.D), dtype=torch.bfloat16, device="cuda")
+                out = torch.full_like(q, float("nan"))
+                lk.lckv_project_qkv(gc.h, l, x.cuda(), hidden, Wd[l][0], Wd[l][1], Wd[l][2], q, gc.lens, wl.B,
+                                    10000.0, ws)
+                lk.lckv_decode_attention(gc.h, l, q, out, gc.lens, None, wl.B, hint, workspace=aws)
+                torch.cuda.synchronize()
+                # the oracle: its own projection (rounded to bf16 as the stored K/V and the query are), then
+                # the definition of the attention on its own cache
+                xf = to_f32_numpy(x)
+                rb = lambda a: to_f32_numpy(torch.from_numpy(a).to(torch.bfloat16))
+                qo = rb(orc.project(xf, to_f32_numpy(W[l][0]), wl.Hq, pos=lens_o))
+                if l in producers:
+                    ko = rb(orc.project(xf, to_f32_numpy(W[l][1]), wl.Hkv, pos=lens_o))
+                    vo = rb(orc.project(xf, to_f32_numpy(W[l][2]), wl.Hkv))
+                    for b in range(wl.B):
+                        Kf[producers[l], b, lens_o[b]], Vf[producers[l], b, lens_o[b]] = ko[b], vo[b]
+                slot, vis = lk.lckv_kv_slot(gc.h, l)
+                n = lens_o + (1 if vis else 0)
+                want = np.zeros((wl.B, wl.Hq, wl.D))
+                for b in range(wl.B):
+                    for h in range(wl.Hq):
+                        g = h // (wl.Hq // wl.Hkv)
+                        want[b, h] = orc.attend(qo[b, h], Kf[slot, b, :n[b], g], Vf[slot, b, :n[b], g], scale)
+                # the two sides round q, k, v to bf16 independently (an ulp apart now and then): looser bar
+                g_ = out.float().cpu().numpy()
+                assert np.isfinite(g_).all()
+                assert np.abs(g_ - want).max() <= 4e-2, "step %d layer %d" % (step, l)
+            gc.lens += 1
+            lens_o += 1
+        assert gc.device_error() == 0
