@@ -178,6 +178,74 @@ def prefill_bench(steps, warmup, tile):
             "max_abs_err_vs_oracle": err, "max_abs_expected": ref}))
 
 
+def project_bench(steps, warmup, batch):
+    """The projections of one decode step (lckv_project_qkv for every layer: queries everywhere, keys and values
+    - rotated and stored into the cache - for the producing layers only), Llama-7B shape, bf16, hidden 4096.
+    Weight-streaming bound: reported against the HBM peak.  Checks sampled outputs against the oracle.
+    Prints one JSON line."""
+    import numpy as np
+    import torch
+    from oracle import lckv_oracle as orc
+    from paper_2405_10637_amd import binding as lk
+    from paper_2405_10637_amd import synth
+    from paper_2405_10637_amd.runner import DecodeSession
+
+    hidden, T = 4096, 64
+    wl = synth.C3.with_(B=batch, T=T, name="project-llama-7b-B%d" % batch)
+    with DecodeSession(wl, room=steps + warmup + 4) as sess:
+        producers = {lk.lckv_slot_producer(sess.h, s): s for s in range(sess.n_slots)}
+        g = torch.Generator(device="cuda")
+        g.manual_seed(wl.seed + 77)
+        rnd = lambda rows: (torch.randn((rows, hidden), generator=g, device="cuda") / hidden ** 0.5).to(torch.bfloat16)
+        W = [(rnd(wl.Hq * wl.D),) + ((rnd(wl.Hkv * wl.D), rnd(wl.Hkv * wl.D)) if l in producers else (None, None))
+             for l in range(wl.L)]
+        x = torch.randn((wl.L, wl.B, hidden), generator=g, device="cuda").to(torch.bfloat16)
+        q = torch.empty((wl.L, wl.B, wl.Hq, wl.D), dtype=torch.bfloat16, device="cuda")
+        ws = torch.empty(lk.lckv_project_workspace_bytes(sess.h, wl.B, hidden), dtype=torch.uint8, device="cuda")
+
+        def one_step():
+            for l in range(wl.L):
+                lk.lckv_project_qkv(sess.h, l, x[l], hidden, W[l][0], W[l][1], W[l][2], q[l], sess.lens, wl.B,
+                                    10000.0, ws)
+
+        one_step()
+        torch.cuda.synchronize()
+        err = ref = 0.0
+        lens = sess.lens.cpu().numpy()
+        f32 = lambda t: t.float().cpu().numpy()
+        for l in sorted(set([0, 1, wl.L // 2] + list(producers))):
+            for b in (0, wl.B - 1):
+                for h in (0, wl.Hq - 1):
+                    want = orc.project(f32(x[l, b:b + 1]), f32(W[l][0][h * wl.D:(h + 1) * wl.D]), 1, pos=lens[b:b + 1])
+                    got = f32(q[l, b, h]).astype(np.float64)
+                    err, ref = max(err, float(np.abs(got - want[0, 0]).max())), max(ref, float(np.abs(want).max()))
+        if err > 2e-2 or err > 1e-2 * max(ref, 1e-3):
+            sys.exit("projection disagrees with the oracle: err %g, max expected %g" % (err, ref))
+        for _ in range(warmup):
+            one_step()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            one_step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        rows = wl.L * wl.Hq * wl.D + 2 * len(producers) * wl.Hkv * wl.D       # weight rows a step streams
+        full = wl.L * (wl.Hq + 2 * wl.Hkv) * wl.D                           # ... with K/V projections everywhere
+        nbytes = 2.0 * rows * hidden + wl.L * wl.B * (hidden + wl.Hq * wl.D) * 2.0
+        gbps = nbytes / (ms * 1e-3) / 1e9
+        print(json.dumps({
+            "metric": "q/k/v projections + rotary embedding + append of one decode step (Llama-7B shape, B=%d)" % batch,
+            "value": wl.B / (ms * 1e-3), "unit": "tokens/s (projections only)", "n_gpus": 1, "steps": steps,
+            "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": wl.name, "hidden": hidden, "producing_layers": sorted(producers)},
+            "roofline": {"bound": "hbm", "kernel": "project_bf16_kernel (+ prepare, finish)", "achieved": gbps,
+                         "peak": 8000.0, "unit": "GB/s", "frac": gbps / 8000.0, "traffic": None},
+            "weight_rows_streamed": rows, "weight_rows_with_kv_everywhere": full,
+            "max_abs_err_vs_oracle": err, "max_abs_expected": ref}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -199,6 +267,9 @@ def main():
     ap.add_argument("--prefill", action="store_true",
                     help="instead of the decode benchmark: prompt-encoding attention of one layer (MFMA-bound)")
     ap.add_argument("--prefill-tile", type=int, default=0, help="query blocks per wave in the prefill kernel (2|4)")
+    ap.add_argument("--project", action="store_true",
+                    help="instead of the decode benchmark: the q/k/v projections of one decode step (HBM-bound)")
+    ap.add_argument("--batch", type=int, default=128, help="sequences in --project")
     ap.add_argument("--residency-sweep", action="store_true",
                     help="instead of the benchmark: effective bandwidth vs size of the shared slot (C2 shape)")
     args = ap.parse_args()
@@ -208,6 +279,8 @@ def main():
         return residency_sweep(args.steps, args.warmup)
     if args.prefill:
         return prefill_bench(args.steps, args.warmup, args.prefill_tile)
+    if args.project:
+        return project_bench(args.steps, args.warmup, args.batch)
 
     import numpy as np
     import torch

@@ -165,8 +165,8 @@ int lckv_set_prefill_tile(lckv_cache *cache, int32_t query_blocks_per_wave);
  * rot_t is the rotary position embedding in the Llama convention (the paper trains Llama models and does not
  * restate it): within a head, channel i < D/2 is paired with channel i + D/2 and the pair is turned by the
  * angle t * rope_base^(-2i/D); rope_base <= 0 means no rotation.  Products are accumulated in fp32 (bf16
- * caches; the order of the partial sums over the hidden dimension is not fixed, so two runs may differ in the
- * last bit before rounding) or in fp64 (fp32 caches), rotated in fp32 and rounded once to the element type.
+ * caches; the hidden dimension is cut into slices whose partial sums are added in a fixed order, so results do
+ * not vary from run to run) or in fp64 (fp32 caches), rotated in fp32 and rounded once to the element type.
  * x: device [B][hidden]; w_q: device [Hq*D][hidden], w_k, w_v: device [Hkv*D][hidden], all in the cache's
  * element type, 16-byte aligned; bf16 needs hidden % 256 == 0.  w_k and w_v must both be given for a producing
  * layer (LCKV_ERR_NULL) and must both be NULL for any other (LCKV_ERR_NOT_PRODUCER: such parameters do not
@@ -174,11 +174,11 @@ int lckv_set_prefill_tile(lckv_cache *cache, int32_t query_blocks_per_wave);
  * at least lckv_project_workspace_bytes; its contents need not be kept between calls.  With the sink + window
  * policy the condensed producing layer is refused (LCKV_ERR_CONFIG): there its K/V must be stored after the
  * layer's own attention (see lckv_append_kv), so project into buffers of your own with a non-producing call
- * pattern or use lckv_step.  Only enqueues (three launches). */
+ * pattern or use lckv_step.  Only enqueues (two launches). */
 int lckv_project_qkv(lckv_cache *cache, int32_t layer, const void *x, int32_t hidden, const void *w_q,
                      const void *w_k, const void *w_v, void *q_out, const int32_t *dev_seq_lens, int32_t B,
                      float rope_base, void *workspace, size_t workspace_bytes, void *hip_stream);
-int lckv_project_workspace_bytes(const lckv_cache *cache, int32_t B, size_t *bytes);
+int lckv_project_workspace_bytes(const lckv_cache *cache, int32_t B, int32_t hidden, size_t *bytes);
 
 /* The whole step: layers in index order (layer l+1 starts after layer l has finished: in the model its query
  * depends on layer l's output); a warmup layer's K/V are appended just before its attention (it sees itself),

@@ -75,7 +75,7 @@ def lib():
         L.lckv_prefill_attention.argtypes = [vp, i32, vp, vp, vp, i32, i32, vp]
         L.lckv_set_prefill_tile.argtypes = [vp, i32]
         L.lckv_project_qkv.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, i32, ctypes.c_float, vp, sz, vp]
-        L.lckv_project_workspace_bytes.argtypes = [vp, i32, ctypes.POINTER(sz)]
+        L.lckv_project_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
         L.lckv_step.argtypes =[vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
         L.lckv_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
         L.lckv_set_split_tokens.argtypes = [vp, i32]
@@ -211,9 +211,9 @@ def lckv_step(cache: int, q_all, k_new_all, v_new_all, out_all, dev_seq_lens, B:
                            max_len_hint, _ptr(workspace), workspace_bytes, _stream(stream)), "lckv_step")
 
 
-def lckv_project_workspace_bytes(cache: int, B: int) -> int:
+def lckv_project_workspace_bytes(cache: int, B: int, hidden: int) -> int:
     out = ctypes.c_size_t(0)
-    _check(lib().lckv_project_workspace_bytes(cache, B, ctypes.byref(out)), "lckv_project_workspace_bytes")
+    _check(lib().lckv_project_workspace_bytes(cache, B, hidden, ctypes.byref(out)), "lckv_project_workspace_bytes")
     return out.value
 
 

@@ -454,17 +454,25 @@ int lckv_workspace_bytes(const lckv_cache *c, int32_t B, int32_t max_len_hint, s
     return LCKV_OK;
 }
 
-// Workspace of lckv_project_qkv: fp32 accumulator [B][(Hq + 2 Hkv) D], then the cos/sin table [B][D/2].
-static size_t project_acc_bytes(const lckv_cache *c, int B) {
-    size_t n = (size_t)B * ((size_t)c->cfg.Hq + 2 * (size_t)c->cfg.Hkv) * c->cfg.D * sizeof(float);
+// Workspace of lckv_project_qkv: fp32 partial sums [slices][B][rows], the larger of a producing layer's
+// (rows = (Hq + 2 Hkv) D) and a non-producing layer's (rows = Hq D, possibly cut into more slices).
+static size_t project_acc_bytes(const lckv_cache *c, int B, int hidden) {
+    const size_t n_kv = ((size_t)c->cfg.Hq + 2 * (size_t)c->cfg.Hkv) * c->cfg.D, n_q = (size_t)c->cfg.Hq * c->cfg.D;
+    size_t slices_kv = 1, slices_q = 1;
+    if (c->cfg.dtype == LCKV_BF16) {
+        slices_kv = (size_t)hidden / project_slice_channels((int)n_kv, hidden);
+        slices_q = (size_t)hidden / project_slice_channels((int)n_q, hidden);
+    }
+    size_t n = slices_kv * n_kv > slices_q * n_q ? slices_kv * n_kv : slices_q * n_q;
+    n *= (size_t)B * sizeof(float);
     return (n + 255) / 256 * 256;
 }
 
-int lckv_project_workspace_bytes(const lckv_cache *c, int32_t B, size_t *bytes) {
+int lckv_project_workspace_bytes(const lckv_cache *c, int32_t B, int32_t hidden, size_t *bytes) {
     if (!valid(c) || !bytes) return LCKV_ERR_NULL;
     if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
-    size_t rope = (size_t)B * (c->cfg.D / 2) * sizeof(float2);
-    *bytes = project_acc_bytes(c, B) + (rope + 255) / 256 * 256;
+    if (hidden < 1 || (c->cfg.dtype == LCKV_BF16 && hidden % 256 != 0)) return LCKV_ERR_CONFIG;
+    *bytes = project_acc_bytes(c, B, hidden);
     return LCKV_OK;
 }
 
@@ -487,12 +495,11 @@ int lckv_project_qkv(lckv_cache *c, int32_t layer, const void *x, int32_t hidden
         (w_k && !aligned(w_k, 16)) || (w_v && !aligned(w_v, 16)))
         return LCKV_ERR_ALIGN;
     size_t need = 0;
-    lckv_project_workspace_bytes(c, B, &need);
+    lckv_project_workspace_bytes(c, B, hidden, &need);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return LCKV_ERR_WORKSPACE;
     float *acc = (float *)workspace;
-    float2 *rope = (float2 *)((char *)workspace + project_acc_bytes(c, B));
     hipError_t e = launch_project(x, hidden, w_q, w_k, w_v, q_out, slot_view(c, slot >= 0 ? slot : 0), dev_seq_lens, B,
-                                  c->cfg.Hq, c->cfg.Hkv, c->cfg.D, c->cfg.dtype, rope_base, acc, rope, c->dev_err,
+                                  c->cfg.Hq, c->cfg.Hkv, c->cfg.D, c->cfg.dtype, rope_base, acc, c->dev_err,
                                   (hipStream_t)hip_stream);
     return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
 }

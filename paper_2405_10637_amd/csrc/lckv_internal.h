@@ -94,9 +94,10 @@ hipError_t launch_bump(int32_t *seq_lens, int B, hipStream_t s);
 hipError_t launch_load_dense(const SlotView &v, const void *k, const void *vv, const int32_t *lens, int B, int T,
                              int D, int dtype,
                              int32_t *dev_err, hipStream_t s);
+int project_slice_channels(int n_total, int hidden);
 hipError_t launch_project(const void *x, int hidden, const void *w_q, const void *w_k, const void *w_v, void *q_out,
                           const SlotView &slot, const int32_t *seq_lens, int B, int Hq, int Hkv, int D, int dtype,
-                          float rope_base, float *acc, float2 *rope, int32_t *dev_err, hipStream_t s);
+                          float rope_base, float *acc, int32_t *dev_err, hipStream_t s);
 hipError_t launch_stream_probe(const void *buf, size_t bytes, int nontemporal, int32_t *sink, hipStream_t s);
 hipError_t launch_gather(const SlotView &v, int b, int pos, int n_pos, int D, int dtype, void *dev_k, void *dev_v,
                          int32_t *dev_err, hipStream_t s);

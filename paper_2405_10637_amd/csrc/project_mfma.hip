@@ -6,27 +6,27 @@
 // head is paired with channel i + D/2, angle t_b * base^(-2i/D)), the queries written to q_out, the keys and
 // values stored straight into the slot at position t_b (the append of the decode step, fused).
 //
-// Three launches on the caller's stream:
-//   1. prepare: clear the fp32 accumulator [B][N] in the workspace, tabulate cos/sin [B][D/2] (angles in double)
-//   2. the matrix product, split over the hidden dimension, partial sums added with fp32 atomics
-//   3. finish: rotate, round once, scatter into q_out / the cache pages
+// Two launches on the caller's stream:
+//   1. the matrix product, split over the hidden dimension into slices; every slice writes its partial sums
+//      [slice][B][N] in fp32 with plain stores (atomic adds from all XCDs onto one accumulator were measured:
+//      they resolve outside the per-XCD L2 and took 35x the time of the weight stream)
+//   2. finish: add the slices in a fixed order, rotate (angles formed in double), round once, scatter into
+//      q_out / the cache pages
 // The product streams each weight once from HBM (what bounds it: 2 * N * hidden bytes against 4 * B flops per
-// weight) and is shaped for that.  A workgroup of 4 waves owns 128 output features x 256 hidden channels x up to
-// 128 sequences: its x slice (64 KiB) is staged once in LDS in matrix-operand order and shared by the waves,
-// each wave owns two 16-feature tiles whose weights it loads straight into registers (all 16 loads of 1 KiB
-// issued before anything else, so 32 KiB per workgroup are in flight), and every LDS read of an x operand feeds
-// two matrix instructions.  Features on the rows of the tiles (A operand = weights, rows of W are contiguous in
-// memory), sequences on the columns.  The order of the contraction index inside a slice is permuted, the same way
-// for both operands, so that each lane's eight 16-byte weight loads are 128 contiguous bytes.
+// weight) and is shaped for that.  A workgroup of 4 waves owns 128 output features x one slice of KSTEPS * 32
+// hidden channels x up to 128 sequences.  Each wave owns two 16-feature tiles whose weights it loads straight
+// into registers, all of them issued before anything else (up to 128 KiB per workgroup in flight); meanwhile the
+// x slice is staged in LDS in matrix-operand order, shared by the waves; after one barrier the wave runs its
+// matrix instructions, each LDS read of an x operand feeding two of them.  Features on the rows of the tiles
+// (A operand = weights: rows of W are contiguous in memory), sequences on the columns.
 #include "bf16_mfma_common.h"
 
 namespace lckv {
 
 namespace {
 
-constexpr int kSliceC = 256;    // hidden channels per workgroup
-constexpr int kSteps = 8;       // matrix instructions (32 channels each) per slice
 constexpr int kTileRows = 128;  // output features per workgroup (8 tiles of 16, two per wave)
+typedef __attribute__((address_space(3))) void *LdsPtr;
 
 struct ProjParams {
     const void *x;              // [B][hidden]
@@ -34,8 +34,8 @@ struct ProjParams {
     int32_t n_rows[3];
     int32_t n_total;            // rows of the stacked matrix
     int32_t hidden, B;
-    float *acc;                 // [B][n_total] fp32
-    float2 *rope;               // [B][D/2] (cos, sin)
+    float *acc;                 // [n_slices][B][n_total] fp32 partial sums
+    int32_t n_slices;
     const int32_t *seq_lens;
     void *q_out;                // [B][Hq][D]
     SlotView slot;              // where K/V go (producing layers)
@@ -44,25 +44,6 @@ struct ProjParams {
     int32_t rotate;
     int32_t *dev_err;
 };
-
-// Launch 1.
-__global__ void project_prepare_kernel(ProjParams p) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t n_acc = (int64_t)p.B * p.n_total;
-    if (i < n_acc) p.acc[i] = 0.f;
-    const int half = p.D / 2;
-    if (i < (int64_t)p.B * half) {
-        const int b = (int)(i / half), k = (int)(i % half);
-        float2 cs = {1.f, 0.f};
-        if (p.rotate) {
-            int t = p.seq_lens[b];
-            if (t < 0) t = 0;
-            const double angle = (double)t * exp2(-2.0 * k / p.D * p.log2_base);
-            cs = float2{(float)cos(angle), (float)sin(angle)};
-        }
-        p.rope[i] = cs;
-    }
-}
 
 // Row n of the stacked matrix -> pointer to that row's first element (rows never straddle: n_rows are multiples
 // of 16 and a tile is 16 rows).
@@ -80,42 +61,56 @@ __device__ __forceinline__ const E *stacked_row(const ProjParams &p, int n) {
     return (const E *)p.w[m] + (int64_t)n * p.hidden;
 }
 
-// Launch 2, bf16.  NB = 16-sequence blocks per pass (1, 2, 4 or 8).  grid (feature blocks, hidden slices,
-// passes of 16 * NB sequences).
-template <int NB>
-__global__ __launch_bounds__(256, 2) void project_bf16_kernel(ProjParams p) {
-    __shared__ __attribute__((aligned(16))) char lds[NB * kSteps * 1024];
+// Launch 1, bf16.  NB = 16-sequence blocks per pass (1, 2, 4 or 8), KSTEPS = matrix instructions (32 hidden
+// channels each) per slice.  grid (feature blocks, slices, passes of 16 * NB sequences).
+template <int NB, int KSTEPS>
+__global__ __launch_bounds__(256, 1) void project_bf16_kernel(ProjParams p) {
+    __shared__ __attribute__((aligned(16))) char lds[NB * KSTEPS * 1024];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, kb = lane >> 4;
-    const int c0 = blockIdx.y * kSliceC;
+    const int c0 = blockIdx.y * (KSTEPS * 32);
     const int b0 = blockIdx.z * (16 * NB);
 
-    // this wave's weights: two tiles x 8 steps, lane (kb, r) takes channels c0 + (kb*8 + s)*8 .. +7 of row r
-    u32x4 wr[2][kSteps];
+    // this wave's weights: two tiles x KSTEPS steps; at step s lane (kb, r) takes channels c0 + 32s + 8kb .. +7
+    // of row r (each load instruction covers 64 contiguous bytes of 16 rows, the KSTEPS loads all of the slice)
+    u32x4 wr[2][KSTEPS];
     bool have[2];
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
         const int n0 = blockIdx.x * kTileRows + (wave * 2 + nt) * 16;
         have[nt] = n0 < p.n_total;  // wave-uniform
         if (have[nt]) {
-            const char *row = (const char *)(stacked_row<uint16_t>(p, n0 + r) + c0 + kb * 64);
+            const char *row = (const char *)(stacked_row<uint16_t>(p, n0 + r) + c0 + kb * 8);
 #pragma unroll
-            for (int s = 0; s < kSteps; ++s) wr[nt][s] = __builtin_nontemporal_load((const u32x4 *)(row + s * 16));
+            for (int s = 0; s < KSTEPS; ++s) wr[nt][s] = __builtin_nontemporal_load((const u32x4 *)(row + s * 64));
         } else {
 #pragma unroll
-            for (int s = 0; s < kSteps; ++s) wr[nt][s] = u32x4{0u, 0u, 0u, 0u};
+            for (int s = 0; s < KSTEPS; ++s) wr[nt][s] = u32x4{0u, 0u, 0u, 0u};
         }
     }
 
-    // the x slice into LDS, operand order: [sequence block][step s][lane (kb, b % 16)][8 channels]
-    for (int i = tid; i < NB * 16 * 32; i += 256) {
-        const int b = i >> 5, c8 = i & 31;  // 16-byte chunk c8 of row b: channels c0 + 8*c8 = c0 + (kb*8 + s)*8
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (b0 + b < p.B) v = *(const u32x4 *)((const uint16_t *)p.x + (int64_t)(b0 + b) * p.hidden + c0 + c8 * 8);
-        const int ckb = c8 >> 3, s = c8 & 7;
-        *(u32x4 *)(lds + ((((b >> 4) * kSteps + s) * 64) + ckb * 16 + (b & 15)) * 16) = v;
+    // the x slice into LDS by direct global-to-LDS loads, operand order [sequence block][step s][lane (kb, b % 16)]
+    // [8 channels]: one load instruction fills the 1 KiB operand of one (sequence block, step), lane (kb, c)
+    // fetching channels c0 + 32s + 8kb .. +7 of sequence b0 + 16j + c (rows past the batch: the last row, whose
+    // columns are never stored).  All of them are in flight together with the weights.  Issued as assembly: the
+    // compiler's builtin would make every LDS read below wait on each of them separately.
+    constexpr int kTiles = NB * KSTEPS;
+    static_assert(kTiles % 4 == 0, "tiles divide among the four waves");
+#pragma unroll
+    for (int k = 0; k < kTiles / 4; ++k) {
+        const int tile = wave + 4 * k, j = tile / KSTEPS, st = tile % KSTEPS;
+        const int b = min(b0 + 16 * j + r, p.B - 1);
+        const uint16_t *src = (const uint16_t *)p.x + (int64_t)b * p.hidden + c0 + st * 32 + kb * 8;
+        const uint32_t dst = (uint32_t)(uintptr_t)(LdsPtr)(lds + tile * 1024);
+        uint32_t m0_saved;  // M0 carries the LDS address; whatever the compiler keeps there is put back
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
+                     "s_mov_b32 m0, %0"
+                     : "=&s"(m0_saved)
+                     : "s"(dst), "v"(src)
+                     : "memory");
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     floatx4 acc[2][NB];
@@ -124,17 +119,18 @@ __global__ __launch_bounds__(256, 2) void project_bf16_kernel(ProjParams p) {
 #pragma unroll
         for (int j = 0; j < NB; ++j) acc[nt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int s = 0; s < kSteps; ++s)
+    for (int s = 0; s < KSTEPS; ++s)
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
-            const bf16x8 xb = __builtin_bit_cast(bf16x8, *(const u32x4 *)(lds + ((j * kSteps + s) * 64 + lane) * 16));
+            const bf16x8 xb = __builtin_bit_cast(bf16x8, *(const u32x4 *)(lds + ((j * KSTEPS + s) * 64 + lane) * 16));
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt)
                 acc[nt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wr[nt][s]), xb,
                                                                      acc[nt][j], 0, 0, 0);
         }
 
-    // lane (kb, c) holds features n0 + 4kb .. +3 of sequence b0 + 16j + c
+    // lane (kb, c) holds features n0 + 4kb .. +3 of sequence b0 + 16j + c: 16 bytes of this slice's partial sums
+    float *part = p.acc + (int64_t)blockIdx.y * p.B * p.n_total;
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
         if (!have[nt]) continue;
@@ -142,15 +138,12 @@ __global__ __launch_bounds__(256, 2) void project_bf16_kernel(ProjParams p) {
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             const int b = b0 + 16 * j + r;
-            if (b >= p.B) continue;
-            float *dst = p.acc + (int64_t)b * p.n_total + n0 + 4 * kb;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dst + e, acc[nt][j][e]);
+            if (b < p.B) *(floatx4 *)(part + (int64_t)b * p.n_total + n0 + 4 * kb) = acc[nt][j];
         }
     }
 }
 
-// Launch 2, fp32 (parity mode, not tuned): one thread per output, products accumulated in double.
+// Launch 1, fp32 (parity mode, not tuned): one thread per output, products accumulated in double.
 __global__ void project_f32_kernel(ProjParams p) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)p.B * p.n_total) return;
@@ -165,21 +158,47 @@ __global__ void project_f32_kernel(ProjParams p) {
 __device__ __forceinline__ uint16_t to_elem(float v, uint16_t) { return (uint16_t)(pack_bf16(v, 0.f) & 0xffffu); }
 __device__ __forceinline__ uint32_t to_elem(float v, uint32_t) { return __builtin_bit_cast(uint32_t, v); }
 
-// Launch 3.  One thread per (sequence, head of the stacked output, channel pair i < D/2).
+template <typename E>
+__device__ __forceinline__ void finish_pair(const ProjParams &p, const float2 *cs_table, int b, int hg, int i);
+
+// Launch 2.  A workgroup takes one sequence and a quarter of the heads of the stacked output; it first tabulates
+// cos/sin of the sequence's D/2 angles (formed in double: position 32767 at the highest frequency is 32767 rad),
+// then each thread finishes channel pairs (head, i < D/2).
 template <typename E>
 __global__ void project_finish_kernel(ProjParams p) {
+    __shared__ float2 cs_table[128];
     const int half = p.D / 2;
     const int heads = p.n_total / p.D;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (int64_t)p.B * heads * half) return;
-    const int i = (int)(idx % half);
-    const int hg = (int)((idx / half) % heads);
-    const int b = (int)(idx / ((int64_t)half * heads));
+    const int b = blockIdx.x;
+    if ((int)threadIdx.x < half) {
+        float2 cs = {1.f, 0.f};
+        if (p.rotate) {
+            int t = p.seq_lens[b];
+            if (t < 0) t = 0;
+            const double angle = (double)t * exp2(-2.0 * (int)threadIdx.x / p.D * p.log2_base);
+            cs = float2{(float)cos(angle), (float)sin(angle)};
+        }
+        cs_table[threadIdx.x] = cs;
+    }
+    __syncthreads();
+    const int per_block = (heads + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int h_begin = blockIdx.y * per_block, h_end = min(h_begin + per_block, heads);
+    for (int item = threadIdx.x; item < (h_end - h_begin) * half; item += blockDim.x)
+        finish_pair<E>(p, cs_table, b, h_begin + item / half, item % half);
+}
+
+template <typename E>
+__device__ __forceinline__ void finish_pair(const ProjParams &p, const float2 *cs_table, int b, int hg, int i) {
+    const int half = p.D / 2;
     const float *y = p.acc + (int64_t)b * p.n_total + (int64_t)hg * p.D;
-    float lo = y[i], hi = y[i + half];
+    float lo = 0.f, hi = 0.f;
+    for (int sl = 0; sl < p.n_slices; ++sl) {  // fixed order: the result does not depend on the launch
+        lo += y[(int64_t)sl * p.B * p.n_total + i];
+        hi += y[(int64_t)sl * p.B * p.n_total + i + half];
+    }
     const bool is_v = hg >= p.Hq + p.Hkv;
     if (!is_v) {
-        const float2 cs = p.rope[(int64_t)b * half + i];
+        const float2 cs = cs_table[i];
         const float rl = lo * cs.x - hi * cs.y, rh = hi * cs.x + lo * cs.y;
         lo = rl;
         hi = rh;
@@ -216,10 +235,17 @@ __global__ void project_finish_kernel(ProjParams p) {
 
 }  // namespace
 
+// Hidden channels per slice for the bf16 product: 512 when that still gives every compute unit a workgroup, else
+// 256 (more, thinner slices).  Needs hidden % 256 == 0.
+int project_slice_channels(int n_total, int hidden) {
+    const int64_t blocks = (n_total + kTileRows - 1) / kTileRows;
+    return (hidden % 512 == 0 && blocks * (hidden / 512) >= 256) ? 512 : 256;
+}
+
 // x [B][hidden]; w_k / w_v null for a layer that produces no slot (then `slot` is not used).
 hipError_t launch_project(const void *x, int hidden, const void *w_q, const void *w_k, const void *w_v, void *q_out,
                           const SlotView &slot, const int32_t *seq_lens, int B, int Hq, int Hkv, int D, int dtype,
-                          float rope_base, float *acc, float2 *rope, int32_t *dev_err, hipStream_t s) {
+                          float rope_base, float *acc, int32_t *dev_err, hipStream_t s) {
     ProjParams p{};
     p.x = x;
     p.w[0] = w_q;
@@ -232,7 +258,6 @@ hipError_t launch_project(const void *x, int hidden, const void *w_q, const void
     p.hidden = hidden;
     p.B = B;
     p.acc = acc;
-    p.rope = rope;
     p.seq_lens = seq_lens;
     p.q_out = q_out;
     p.slot = slot;
@@ -244,26 +269,34 @@ hipError_t launch_project(const void *x, int hidden, const void *w_q, const void
     p.dev_err = dev_err;
 
     const int64_t n_acc = (int64_t)B * p.n_total;
-    hipLaunchKernelGGL(project_prepare_kernel, dim3((unsigned)((n_acc + 255) / 256)), dim3(256), 0, s, p);
     if (dtype == LCKV_BF16) {
         const int per_pass = B > 64 ? 128 : B > 32 ? 64 : B > 16 ? 32 : 16;
-        dim3 grid((p.n_total + kTileRows - 1) / kTileRows, hidden / kSliceC, (B + per_pass - 1) / per_pass);
-        if (per_pass == 128)
-            hipLaunchKernelGGL(project_bf16_kernel<8>, grid, dim3(256), 0, s, p);
-        else if (per_pass == 64)
-            hipLaunchKernelGGL(project_bf16_kernel<4>, grid, dim3(256), 0, s, p);
-        else if (per_pass == 32)
-            hipLaunchKernelGGL(project_bf16_kernel<2>, grid, dim3(256), 0, s, p);
-        else
-            hipLaunchKernelGGL(project_bf16_kernel<1>, grid, dim3(256), 0, s, p);
+        const int ksteps = project_slice_channels(p.n_total, hidden) / 32;
+        p.n_slices = hidden / (ksteps * 32);
+        dim3 grid((p.n_total + kTileRows - 1) / kTileRows, p.n_slices, (B + per_pass - 1) / per_pass);
+#define LCKV_PROJECT_LAUNCH(NB)                                                              \
+    if (ksteps == 16)                                                                        \
+        hipLaunchKernelGGL((project_bf16_kernel<NB, 16>), grid, dim3(256), 0, s, p);        \
+    else                                                                                     \
+        hipLaunchKernelGGL((project_bf16_kernel<NB, 8>), grid, dim3(256), 0, s, p)
+        if (per_pass == 128) {
+            LCKV_PROJECT_LAUNCH(8);
+        } else if (per_pass == 64) {
+            LCKV_PROJECT_LAUNCH(4);
+        } else if (per_pass == 32) {
+            LCKV_PROJECT_LAUNCH(2);
+        } else {
+            LCKV_PROJECT_LAUNCH(1);
+        }
+#undef LCKV_PROJECT_LAUNCH
     } else {
+        p.n_slices = 1;
         hipLaunchKernelGGL(project_f32_kernel, dim3((unsigned)((n_acc + 255) / 256)), dim3(256), 0, s, p);
     }
-    const int64_t n_fin = n_acc / 2;
     if (dtype == LCKV_BF16)
-        hipLaunchKernelGGL(project_finish_kernel<uint16_t>, dim3((unsigned)((n_fin + 255) / 256)), dim3(256), 0, s, p);
+        hipLaunchKernelGGL(project_finish_kernel<uint16_t>, dim3(B, 4), dim3(256), 0, s, p);
     else
-        hipLaunchKernelGGL(project_finish_kernel<uint32_t>, dim3((unsigned)((n_fin + 255) / 256)), dim3(256), 0, s, p);
+        hipLaunchKernelGGL(project_finish_kernel<uint32_t>, dim3(B, 4), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 

@@ -37,7 +37,7 @@ def run_project(wl, hidden, lens, T_cap, rope_base=10000.0):
           "paged", wl.paged, "base", rope_base, flush=True)
     lens = np.asarray(lens, np.int32)
     with GpuCache(wl, T_cap, lens) as gc:
-        ws = torch.empty(lk.lckv_project_workspace_bytes(gc.h, wl.B), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(lk.lckv_project_workspace_bytes(gc.h, wl.B, hidden), dtype=torch.uint8, device="cuda")
         ws.fill_(0xFF)                                            # the call must not rely on a cleared workspace
         producers = {lk.lckv_slot_producer(gc.h, s): s for s in range(gc.n_slots)}
         pos = lens if rope_base > 0 else None
@@ -111,7 +111,7 @@ def test_project_argument_errors():
     with GpuCache(wl, 32, np.array([3, 4], np.int32)) as gc:
         L = lk.lib()
         t = torch.zeros(1 << 16, dtype=torch.bfloat16, device="cuda")
-        ws = torch.empty(lk.lckv_project_workspace_bytes(gc.h, 2), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(lk.lckv_project_workspace_bytes(gc.h, 2, 256), dtype=torch.uint8, device="cuda")
         p, w, n = t.data_ptr(), ws.data_ptr(), ws.numel()
         st = torch.cuda.current_stream().cuda_stream or None
         call = lambda layer, hidden=256, wk=p, wv=p, B=2, wsp=w, wsn=n: L.lckv_project_qkv(
@@ -149,7 +149,7 @@ def test_decode_steps_from_hidden_states():
         producers = {lk.lckv_slot_producer(gc.h, s): s for s in range(ns)}
         W = [weights(wl, hidden, l, l in producers) for l in range(wl.L)]
         Wd = [[None if t is None else t.cuda() for t in w] for w in W]
-        ws = torch.empty(lk.lckv_project_workspace_bytes(gc.h, wl.B), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(lk.lckv_project_workspace_bytes(gc.h, wl.B, hidden), dtype=torch.uint8, device="cuda")
         lens_o = lens.copy()
         for step in range(steps):
             hint = int(lens_o.max())
