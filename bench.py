@@ -198,14 +198,23 @@ def project_bench(steps, warmup, batch):
         g.manual_seed(wl.seed + 77)
         rnd = lambda rows: (torch.randn((rows, hidden), generator=g, device="cuda") / hidden ** 0.5).to(torch.bfloat16)
         W = [(rnd(wl.Hq * wl.D),) + ((rnd(wl.Hkv * wl.D), rnd(wl.Hkv * wl.D)) if l in producers else (None, None))
-             for l in range(wl.L)]
+             for l in range(wl.L)]                                           # row-major, as the oracle takes them
+
+        def pack(w):                                                        # once, as at model load
+            if w is None:
+                return None
+            wp = torch.empty_like(w)
+            lk.lckv_pack_projection_weight(sess.h, w, wp, w.shape[0], hidden)
+            return wp
+
+        Wp = [tuple(pack(w) for w in ws_) for ws_ in W]
         x = torch.randn((wl.L, wl.B, hidden), generator=g, device="cuda").to(torch.bfloat16)
         q = torch.empty((wl.L, wl.B, wl.Hq, wl.D), dtype=torch.bfloat16, device="cuda")
         ws = torch.empty(lk.lckv_project_workspace_bytes(sess.h, wl.B, hidden), dtype=torch.uint8, device="cuda")
 
         def one_step():
             for l in range(wl.L):
-                lk.lckv_project_qkv(sess.h, l, x[l], hidden, W[l][0], W[l][1], W[l][2], q[l], sess.lens, wl.B,
+                lk.lckv_project_qkv(sess.h, l, x[l], hidden, Wp[l][0], Wp[l][1], Wp[l][2], q[l], sess.lens, wl.B,
                                     10000.0, ws)
 
         one_step()

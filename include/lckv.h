@@ -167,8 +167,8 @@ int lckv_set_prefill_tile(lckv_cache *cache, int32_t query_blocks_per_wave);
  * angle t * rope_base^(-2i/D); rope_base <= 0 means no rotation.  Products are accumulated in fp32 (bf16
  * caches; the hidden dimension is cut into slices whose partial sums are added in a fixed order, so results do
  * not vary from run to run) or in fp64 (fp32 caches), rotated in fp32 and rounded once to the element type.
- * x: device [B][hidden]; w_q: device [Hq*D][hidden], w_k, w_v: device [Hkv*D][hidden], all in the cache's
- * element type, 16-byte aligned; bf16 needs hidden % 256 == 0.  w_k and w_v must both be given for a producing
+ * x: device [B][hidden] in the cache's element type; w_q (Hq*D rows), w_k, w_v (Hkv*D rows): device, PACKED by
+ * lckv_pack_projection_weight, 16-byte aligned; bf16 needs hidden % 256 == 0.  w_k and w_v must both be given for a producing
  * layer (LCKV_ERR_NULL) and must both be NULL for any other (LCKV_ERR_NOT_PRODUCER: such parameters do not
  * exist).  q_out: device [B][Hq][D].  dev_seq_lens: read, not changed.  workspace: device, 256-byte aligned,
  * at least lckv_project_workspace_bytes; its contents need not be kept between calls.  With the sink + window
@@ -179,6 +179,13 @@ int lckv_project_qkv(lckv_cache *cache, int32_t layer, const void *x, int32_t hi
                      const void *w_k, const void *w_v, void *q_out, const int32_t *dev_seq_lens, int32_t B,
                      float rope_base, void *workspace, size_t workspace_bytes, void *hip_stream);
 int lckv_project_workspace_bytes(const lckv_cache *cache, int32_t B, int32_t hidden, size_t *bytes);
+/* Weights are handed to lckv_project_qkv in the order the matrix instructions take them (made once, when the
+ * model is loaded).  w: device [n_rows][hidden] row-major ("out features x in features"), n_rows % 16 == 0;
+ * w_packed: device, same size, must not overlap w.  bf16: tiles of 16 rows, each tile
+ * [hidden/32 steps][4 channel octets kb][16 rows r][8 channels] (lane kb*16 + r of a wave holds channels
+ * 32*step + 8*kb .. +7 of row r), a tile's image contiguous; fp32: a plain copy.  Only enqueues. */
+int lckv_pack_projection_weight(const lckv_cache *cache, const void *w, void *w_packed, int32_t n_rows,
+                                int32_t hidden, void *hip_stream);
 
 /* The whole step: layers in index order (layer l+1 starts after layer l has finished: in the model its query
  * depends on layer l's output); a warmup layer's K/V are appended just before its attention (it sees itself),

@@ -26,7 +26,7 @@ LCKV_LOAD_AUTO, LCKV_LOAD_TEMPORAL, LCKV_LOAD_NONTEMPORAL = 0, 1, 2
 EXPORTS = [
     "lckv_cache_bytes", "lckv_plan_max_batch", "lckv_cache_alloc", "lckv_cache_free", "lckv_cache_set_block_table", "lckv_n_slots",
     "lckv_kv_slot", "lckv_slot_producer", "lckv_append_kv", "lckv_decode_attention", "lckv_prefill_attention",
-    "lckv_set_prefill_tile", "lckv_project_qkv", "lckv_project_workspace_bytes", "lckv_step",
+    "lckv_set_prefill_tile", "lckv_project_qkv", "lckv_project_workspace_bytes", "lckv_pack_projection_weight", "lckv_step",
     "lckv_workspace_bytes", "lckv_set_split_tokens", "lckv_set_load_policy", "lckv_cache_load_dense", "lckv_cache_read",
     "lckv_last_device_error", "lckv_profile_enable", "lckv_profile_read", "lckv_profile_launch_ms",
     "lckv_hbm_read_probe", "lckv_strerror",
@@ -76,6 +76,7 @@ def lib():
         L.lckv_set_prefill_tile.argtypes = [vp, i32]
         L.lckv_project_qkv.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, i32, ctypes.c_float, vp, sz, vp]
         L.lckv_project_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
+        L.lckv_pack_projection_weight.argtypes = [vp, vp, vp, i32, i32, vp]
         L.lckv_step.argtypes =[vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
         L.lckv_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
         L.lckv_set_split_tokens.argtypes = [vp, i32]
@@ -209,6 +210,11 @@ def lckv_step(cache: int, q_all, k_new_all, v_new_all, out_all, dev_seq_lens, B:
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lckv_step(cache, _ptr(q_all), _ptr(k_new_all), _ptr(v_new_all), _ptr(out_all), _ptr(dev_seq_lens), B,
                            max_len_hint, _ptr(workspace), workspace_bytes, _stream(stream)), "lckv_step")
+
+
+def lckv_pack_projection_weight(cache: int, w, w_packed, n_rows: int, hidden: int, stream=None):
+    _check(lib().lckv_pack_projection_weight(cache, _ptr(w), _ptr(w_packed), n_rows, hidden, _stream(stream)),
+           "lckv_pack_projection_weight")
 
 
 def lckv_project_workspace_bytes(cache: int, B: int, hidden: int) -> int:

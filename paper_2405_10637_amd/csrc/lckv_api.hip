@@ -468,6 +468,18 @@ static size_t project_acc_bytes(const lckv_cache *c, int B, int hidden) {
     return (n + 255) / 256 * 256;
 }
 
+int lckv_pack_projection_weight(const lckv_cache *c, const void *w, void *w_packed, int32_t n_rows, int32_t hidden,
+                                void *hip_stream) {
+    if (!valid(c) || !w || !w_packed) return LCKV_ERR_NULL;
+    if (n_rows < 16 || n_rows % 16 != 0 || hidden < 1 || (int64_t)n_rows * hidden > ((int64_t)1 << 40))
+        return LCKV_ERR_CONFIG;
+    if (c->cfg.dtype == LCKV_BF16 && hidden % 256 != 0) return LCKV_ERR_CONFIG;
+    if (!aligned(w, 16) || !aligned(w_packed, 16)) return LCKV_ERR_ALIGN;
+    if (w == w_packed) return LCKV_ERR_CONFIG;
+    hipError_t e = launch_pack_weight(w, w_packed, n_rows, hidden, c->cfg.dtype, (hipStream_t)hip_stream);
+    return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
+}
+
 int lckv_project_workspace_bytes(const lckv_cache *c, int32_t B, int32_t hidden, size_t *bytes) {
     if (!valid(c) || !bytes) return LCKV_ERR_NULL;
     if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;

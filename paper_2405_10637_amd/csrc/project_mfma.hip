@@ -14,11 +14,14 @@
 //      q_out / the cache pages
 // The product streams each weight once from HBM (what bounds it: 2 * N * hidden bytes against 4 * B flops per
 // weight) and is shaped for that.  A workgroup of 4 waves owns 128 output features x one slice of KSTEPS * 32
-// hidden channels x up to 128 sequences.  Each wave owns two 16-feature tiles whose weights it loads straight
+// hidden channels x up to 128 sequences (in two rounds of 64).  Each wave owns two 16-feature tiles whose weights it loads straight
 // into registers, all of them issued before anything else (up to 128 KiB per workgroup in flight); meanwhile the
 // x slice is staged in LDS in matrix-operand order, shared by the waves; after one barrier the wave runs its
 // matrix instructions, each LDS read of an x operand feeding two of them.  Features on the rows of the tiles
-// (A operand = weights: rows of W are contiguous in memory), sequences on the columns.
+// (A operand = weights), sequences on the columns.  The weights are taken in a packed image (made once, when
+// the model is loaded, by the pack kernel below) whose tiles are in matrix-operand order, so that every load
+// instruction is a contiguous KiB, as for the cache pages: with row-major weights an instruction touched 64
+// bytes of 16 rows and the stream reached 2.0 TB/s at best.
 #include "bf16_mfma_common.h"
 
 namespace lckv {
@@ -61,19 +64,52 @@ __device__ __forceinline__ const E *stacked_row(const ProjParams &p, int n) {
     return (const E *)p.w[m] + (int64_t)n * p.hidden;
 }
 
+// Tile (16 rows) t of the stacked matrix -> its packed bf16 image: [hidden/32 steps][64 lanes][8 channels], lane
+// (kb, r) of step s holding channels 32s + 8kb .. +7 of row r, i.e. the A operands of the tile in the order and
+// lane layout the matrix instruction takes them; a tile's image is contiguous (hidden * 32 bytes).
+__device__ __forceinline__ const char *stacked_tile(const ProjParams &p, int t) {
+    int m = 0;
+    if (t >= p.n_rows[0] / 16) {
+        t -= p.n_rows[0] / 16;
+        m = 1;
+        if (t >= p.n_rows[1] / 16) {
+            t -= p.n_rows[1] / 16;
+            m = 2;
+        }
+    }
+    return (const char *)p.w[m] + (int64_t)t * p.hidden * 32;
+}
+
+// Row-major [N][hidden] bf16 -> the packed image above.  One thread per 16-byte chunk.
+__global__ void pack_weight_bf16_kernel(const uint16_t *src, uint16_t *dst, int N, int hidden) {
+    const int chunks_per_row = hidden / 8;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)N * chunks_per_row) return;
+    const int n = (int)(i / chunks_per_row), ch = (int)(i % chunks_per_row);
+    const int t = n >> 4, r = n & 15, s = ch >> 2, kb = ch & 3;
+    const u32x4 v = *(const u32x4 *)(src + (int64_t)n * hidden + ch * 8);
+    *(u32x4 *)(dst + (((int64_t)t * (hidden / 32) + s) * 64 + kb * 16 + r) * 8) = v;
+}
+
 // Launch 1, bf16.  NB = 16-sequence blocks per pass (1, 2, 4 or 8), KSTEPS = matrix instructions (32 hidden
 // channels each) per slice.  grid (feature blocks, slices, passes of 16 * NB sequences).
 template <int NB, int KSTEPS>
-__global__ __launch_bounds__(256, 1) void project_bf16_kernel(ProjParams p) {
-    __shared__ __attribute__((aligned(16))) char lds[NB * KSTEPS * 1024];
+__global__ __launch_bounds__(256, 2) void project_bf16_kernel(ProjParams p, int rounds) {
+    // The x slice in LDS.  With 512-channel slices a sequence's slice is 1 KiB = one fully coalesced load
+    // instruction, so it is kept row-major, rows 1 KiB + 16 bytes apart: lane (kb, c) then reads its operand of
+    // step s at row c, byte 64s + 16kb, and the 16 lanes of a quarter wave fall on 16 different bank quadruples.
+    // With 256-channel slices the image is in operand order (each instruction gathers 64 bytes of 16 sequences).
+    constexpr bool kRowMajor = KSTEPS == 16;
+    constexpr int kRowStride = KSTEPS * 64 + 16;
+    __shared__ __attribute__((aligned(16))) char lds[kRowMajor ? NB * 16 * kRowStride : NB * KSTEPS * 1024];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, kb = lane >> 4;
     const int c0 = blockIdx.y * (KSTEPS * 32);
-    const int b0 = blockIdx.z * (16 * NB);
+    static_assert(NB * KSTEPS % 4 == 0, "tiles divide among the four waves");
 
-    // this wave's weights: two tiles x KSTEPS steps; at step s lane (kb, r) takes channels c0 + 32s + 8kb .. +7
-    // of row r (each load instruction covers 64 contiguous bytes of 16 rows, the KSTEPS loads all of the slice)
+    // this wave's weights: two tiles x KSTEPS steps, from the packed image: every load instruction is one
+    // contiguous, lane-ordered KiB and the KSTEPS loads of a tile are consecutive KiBs
     u32x4 wr[2][KSTEPS];
     bool have[2];
 #pragma unroll
@@ -81,64 +117,84 @@ __global__ __launch_bounds__(256, 1) void project_bf16_kernel(ProjParams p) {
         const int n0 = blockIdx.x * kTileRows + (wave * 2 + nt) * 16;
         have[nt] = n0 < p.n_total;  // wave-uniform
         if (have[nt]) {
-            const char *row = (const char *)(stacked_row<uint16_t>(p, n0 + r) + c0 + kb * 8);
+            const char *img = stacked_tile(p, n0 >> 4) + ((int64_t)(c0 / 32) * 64 + lane) * 16;
 #pragma unroll
-            for (int s = 0; s < KSTEPS; ++s) wr[nt][s] = __builtin_nontemporal_load((const u32x4 *)(row + s * 64));
+            for (int s = 0; s < KSTEPS; ++s) wr[nt][s] = __builtin_nontemporal_load((const u32x4 *)(img + s * 1024));
         } else {
 #pragma unroll
             for (int s = 0; s < KSTEPS; ++s) wr[nt][s] = u32x4{0u, 0u, 0u, 0u};
         }
     }
 
-    // the x slice into LDS by direct global-to-LDS loads, operand order [sequence block][step s][lane (kb, b % 16)]
-    // [8 channels]: one load instruction fills the 1 KiB operand of one (sequence block, step), lane (kb, c)
-    // fetching channels c0 + 32s + 8kb .. +7 of sequence b0 + 16j + c (rows past the batch: the last row, whose
-    // columns are never stored).  All of them are in flight together with the weights.  Issued as assembly: the
-    // compiler's builtin would make every LDS read below wait on each of them separately.
-    constexpr int kTiles = NB * KSTEPS;
-    static_assert(kTiles % 4 == 0, "tiles divide among the four waves");
-#pragma unroll
-    for (int k = 0; k < kTiles / 4; ++k) {
-        const int tile = wave + 4 * k, j = tile / KSTEPS, st = tile % KSTEPS;
-        const int b = min(b0 + 16 * j + r, p.B - 1);
-        const uint16_t *src = (const uint16_t *)p.x + (int64_t)b * p.hidden + c0 + st * 32 + kb * 8;
-        const uint32_t dst = (uint32_t)(uintptr_t)(LdsPtr)(lds + tile * 1024);
-        uint32_t m0_saved;  // M0 carries the LDS address; whatever the compiler keeps there is put back
-        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
-                     "s_mov_b32 m0, %0"
-                     : "=&s"(m0_saved)
-                     : "s"(dst), "v"(src)
-                     : "memory");
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-
-    floatx4 acc[2][NB];
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-        for (int j = 0; j < NB; ++j) acc[nt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s)
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            const bf16x8 xb = __builtin_bit_cast(bf16x8, *(const u32x4 *)(lds + ((j * KSTEPS + s) * 64 + lane) * 16));
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
-                acc[nt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wr[nt][s]), xb,
-                                                                     acc[nt][j], 0, 0, 0);
-        }
-
-    // lane (kb, c) holds features n0 + 4kb .. +3 of sequence b0 + 16j + c: 16 bytes of this slice's partial sums
+    // The weights stay in registers while the sequences of this pass go by in rounds of 16 * NB (the x slice of
+    // more would not leave LDS for a second workgroup on the compute unit, and it is the other workgroup that
+    // computes while this one waits for its loads).
     float *part = p.acc + (int64_t)blockIdx.y * p.B * p.n_total;
+    for (int round = 0; round < rounds; ++round) {
+        const int b0 = (blockIdx.z * rounds + round) * (16 * NB);
+        if (b0 >= p.B) break;  // uniform
+        // The x slice into LDS by direct global-to-LDS loads (issued as assembly: the compiler's builtin would make
+        // every LDS read below wait on each of them separately).  Rows past the batch: the last row, whose columns
+        // are never stored.
+        if (round > 0) asm volatile("s_barrier" ::: "memory");  // everyone has finished reading the last slice
+        auto dma = [&](const uint16_t *src, const char *dst_lds) {  // lane l's 16 bytes land at dst_lds + 16 l
+            const uint32_t dst = (uint32_t)(uintptr_t)(LdsPtr)dst_lds;
+            uint32_t m0_saved;  // M0 carries the LDS address; whatever the compiler keeps there is put back
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
+                         "s_mov_b32 m0, %0"
+                         : "=&s"(m0_saved)
+                         : "s"(dst), "v"(src)
+                         : "memory");
+        };
+        if (kRowMajor) {
+            // a sequence's slice is 1 KiB: one instruction per sequence, rows kRowStride apart in LDS
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        if (!have[nt]) continue;
-        const int n0 = blockIdx.x * kTileRows + (wave * 2 + nt) * 16;
+            for (int k = 0; k < 4 * NB; ++k) {
+                const int row = wave + 4 * k;
+                dma((const uint16_t *)p.x + (int64_t)min(b0 + row, p.B - 1) * p.hidden + c0 + lane * 8,
+                    lds + row * kRowStride);
+            }
+        } else {
+            // operand order [sequence block][step s][lane (kb, b % 16)][8 channels]: one instruction fills the 1 KiB
+            // operand of one (sequence block, step), lane (kb, c) fetching channels c0 + 32s + 8kb .. +7 of sequence
+            // b0 + 16j + c
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            const int b = b0 + 16 * j + r;
-            if (b < p.B) *(floatx4 *)(part + (int64_t)b * p.n_total + n0 + 4 * kb) = acc[nt][j];
+            for (int k = 0; k < NB * KSTEPS / 4; ++k) {
+                const int tile = wave + 4 * k, j = tile / KSTEPS, st = tile % KSTEPS;
+                dma((const uint16_t *)p.x + (int64_t)min(b0 + 16 * j + r, p.B - 1) * p.hidden + c0 + st * 32 + kb * 8,
+                    lds + tile * 1024);
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+
+        floatx4 acc[2][NB];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int j = 0; j < NB; ++j) acc[nt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s)
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const char *xp = kRowMajor ? lds + (16 * j + r) * kRowStride + (4 * s + kb) * 16
+                                           : lds + ((j * KSTEPS + s) * 64 + lane) * 16;
+                const bf16x8 xb = __builtin_bit_cast(bf16x8, *(const u32x4 *)xp);
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                    acc[nt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wr[nt][s]), xb,
+                                                                         acc[nt][j], 0, 0, 0);
+            }
+
+        // lane (kb, c) holds features n0 + 4kb .. +3 of sequence b0 + 16j + c: 16 bytes of this slice's partial sums
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            if (!have[nt]) continue;
+            const int n0 = blockIdx.x * kTileRows + (wave * 2 + nt) * 16;
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const int b = b0 + 16 * j + r;
+                if (b < p.B) *(floatx4 *)(part + (int64_t)b * p.n_total + n0 + 4 * kb) = acc[nt][j];
+            }
         }
     }
 }
@@ -159,46 +215,41 @@ __device__ __forceinline__ uint16_t to_elem(float v, uint16_t) { return (uint16_
 __device__ __forceinline__ uint32_t to_elem(float v, uint32_t) { return __builtin_bit_cast(uint32_t, v); }
 
 template <typename E>
-__device__ __forceinline__ void finish_pair(const ProjParams &p, const float2 *cs_table, int b, int hg, int i);
+__device__ __forceinline__ void finish_pair(const ProjParams &p, float2 cs, int b, int hg, int i);
 
-// Launch 2.  A workgroup takes one sequence and a quarter of the heads of the stacked output; it first tabulates
-// cos/sin of the sequence's D/2 angles (formed in double: position 32767 at the highest frequency is 32767 rad),
-// then each thread finishes channel pairs (head, i < D/2).
+// Launch 2.  One thread per (sequence, head of the stacked output, channel pair i < D/2): adds the slices, forms
+// the angle in double (position 32767 at the highest frequency is 32767 rad), rotates, stores.
 template <typename E>
 __global__ void project_finish_kernel(ProjParams p) {
-    __shared__ float2 cs_table[128];
     const int half = p.D / 2;
     const int heads = p.n_total / p.D;
-    const int b = blockIdx.x;
-    if ((int)threadIdx.x < half) {
-        float2 cs = {1.f, 0.f};
-        if (p.rotate) {
-            int t = p.seq_lens[b];
-            if (t < 0) t = 0;
-            const double angle = (double)t * exp2(-2.0 * (int)threadIdx.x / p.D * p.log2_base);
-            cs = float2{(float)cos(angle), (float)sin(angle)};
-        }
-        cs_table[threadIdx.x] = cs;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)p.B * heads * half) return;
+    const int i = (int)(idx % half);
+    const int hg = (int)((idx / half) % heads);
+    const int b = (int)(idx / ((int64_t)half * heads));
+    float2 cs = {1.f, 0.f};
+    if (p.rotate && hg < p.Hq + p.Hkv) {
+        int t = p.seq_lens[b];
+        if (t < 0) t = 0;
+        const double angle = (double)t * exp2(-2.0 * i / p.D * p.log2_base);
+        cs = float2{(float)cos(angle), (float)sin(angle)};
     }
-    __syncthreads();
-    const int per_block = (heads + (int)gridDim.y - 1) / (int)gridDim.y;
-    const int h_begin = blockIdx.y * per_block, h_end = min(h_begin + per_block, heads);
-    for (int item = threadIdx.x; item < (h_end - h_begin) * half; item += blockDim.x)
-        finish_pair<E>(p, cs_table, b, h_begin + item / half, item % half);
+    finish_pair<E>(p, cs, b, hg, i);
 }
 
 template <typename E>
-__device__ __forceinline__ void finish_pair(const ProjParams &p, const float2 *cs_table, int b, int hg, int i) {
+__device__ __forceinline__ void finish_pair(const ProjParams &p, float2 cs, int b, int hg, int i) {
     const int half = p.D / 2;
     const float *y = p.acc + (int64_t)b * p.n_total + (int64_t)hg * p.D;
     float lo = 0.f, hi = 0.f;
+#pragma unroll 8
     for (int sl = 0; sl < p.n_slices; ++sl) {  // fixed order: the result does not depend on the launch
         lo += y[(int64_t)sl * p.B * p.n_total + i];
         hi += y[(int64_t)sl * p.B * p.n_total + i + half];
     }
     const bool is_v = hg >= p.Hq + p.Hkv;
     if (!is_v) {
-        const float2 cs = cs_table[i];
         const float rl = lo * cs.x - hi * cs.y, rh = hi * cs.x + lo * cs.y;
         lo = rl;
         hi = rh;
@@ -235,6 +286,16 @@ __device__ __forceinline__ void finish_pair(const ProjParams &p, const float2 *c
 
 }  // namespace
 
+hipError_t launch_pack_weight(const void *src, void *dst, int N, int hidden, int dtype, hipStream_t s) {
+    if (dtype == LCKV_BF16) {
+        const int64_t chunks = (int64_t)N * (hidden / 8);
+        hipLaunchKernelGGL(pack_weight_bf16_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s,
+                           (const uint16_t *)src, (uint16_t *)dst, N, hidden);
+        return hipGetLastError();
+    }
+    return hipMemcpyAsync(dst, src, (size_t)N * hidden * 4, hipMemcpyDeviceToDevice, s);  // fp32: row-major as is
+}
+
 // Hidden channels per slice for the bf16 product: 512 when that still gives every compute unit a workgroup, else
 // 256 (more, thinner slices).  Needs hidden % 256 == 0.
 int project_slice_channels(int n_total, int hidden) {
@@ -270,20 +331,20 @@ hipError_t launch_project(const void *x, int hidden, const void *w_q, const void
 
     const int64_t n_acc = (int64_t)B * p.n_total;
     if (dtype == LCKV_BF16) {
-        const int per_pass = B > 64 ? 128 : B > 32 ? 64 : B > 16 ? 32 : 16;
+        // up to 64 sequences per round, up to two rounds per workgroup (the weights are read once per 128 sequences)
+        const int per_round = B > 32 ? 64 : B > 16 ? 32 : 16;
+        const int rounds = B > 64 ? 2 : 1;
         const int ksteps = project_slice_channels(p.n_total, hidden) / 32;
         p.n_slices = hidden / (ksteps * 32);
-        dim3 grid((p.n_total + kTileRows - 1) / kTileRows, p.n_slices, (B + per_pass - 1) / per_pass);
-#define LCKV_PROJECT_LAUNCH(NB)                                                              \
-    if (ksteps == 16)                                                                        \
-        hipLaunchKernelGGL((project_bf16_kernel<NB, 16>), grid, dim3(256), 0, s, p);        \
-    else                                                                                     \
-        hipLaunchKernelGGL((project_bf16_kernel<NB, 8>), grid, dim3(256), 0, s, p)
-        if (per_pass == 128) {
-            LCKV_PROJECT_LAUNCH(8);
-        } else if (per_pass == 64) {
+        dim3 grid((p.n_total + kTileRows - 1) / kTileRows, p.n_slices, (B + per_round * rounds - 1) / (per_round * rounds));
+#define LCKV_PROJECT_LAUNCH(NB)                                                                    \
+    if (ksteps == 16)                                                                              \
+        hipLaunchKernelGGL((project_bf16_kernel<NB, 16>), grid, dim3(256), 0, s, p, rounds);       \
+    else                                                                                           \
+        hipLaunchKernelGGL((project_bf16_kernel<NB, 8>), grid, dim3(256), 0, s, p, rounds)
+        if (per_round == 64) {
             LCKV_PROJECT_LAUNCH(4);
-        } else if (per_pass == 32) {
+        } else if (per_round == 32) {
             LCKV_PROJECT_LAUNCH(2);
         } else {
             LCKV_PROJECT_LAUNCH(1);
@@ -294,9 +355,9 @@ hipError_t launch_project(const void *x, int hidden, const void *w_q, const void
         hipLaunchKernelGGL(project_f32_kernel, dim3((unsigned)((n_acc + 255) / 256)), dim3(256), 0, s, p);
     }
     if (dtype == LCKV_BF16)
-        hipLaunchKernelGGL(project_finish_kernel<uint16_t>, dim3(B, 4), dim3(256), 0, s, p);
+        hipLaunchKernelGGL(project_finish_kernel<uint16_t>, dim3((unsigned)((n_acc / 2 + 255) / 256)), dim3(256), 0, s, p);
     else
-        hipLaunchKernelGGL(project_finish_kernel<uint32_t>, dim3(B, 4), dim3(256), 0, s, p);
+        hipLaunchKernelGGL(project_finish_kernel<uint32_t>, dim3((unsigned)((n_acc / 2 + 255) / 256)), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 

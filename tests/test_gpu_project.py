@@ -32,6 +32,16 @@ def weights(wl, hidden, layer, producer):
     return wq, n(wl.Hkv * wl.D, wl.seed + 100 * layer + 2), n(wl.Hkv * wl.D, wl.seed + 100 * layer + 3)
 
 
+def packed(h, w):
+    """Row-major weight (CPU tensor) -> the device image lckv_project_qkv takes."""
+    if w is None:
+        return None
+    wd = w.cuda().contiguous()
+    wp = torch.full_like(wd, float("nan"))
+    lk.lckv_pack_projection_weight(h, wd, wp, w.shape[0], w.shape[1])
+    return wp
+
+
 def run_project(wl, hidden, lens, T_cap, rope_base=10000.0):
     print("project case", wl.name, wl.dtype, "H", wl.Hq, wl.Hkv, "D", wl.D, "hidden", hidden, "lens", list(lens)[:8],
           "paged", wl.paged, "base", rope_base, flush=True)
@@ -44,7 +54,7 @@ def run_project(wl, hidden, lens, T_cap, rope_base=10000.0):
         for layer in range(wl.L):
             x = synth._normal((wl.B, hidden), 1.0, wl.torch_dtype, wl.seed + 7 * layer)
             wq, wk, wv = weights(wl, hidden, layer, layer in producers)
-            dev = lambda t: None if t is None else t.cuda()
+            dev = lambda t: packed(gc.h, t)
             before = gc.storage.clone()
             q_out = torch.full((wl.B, wl.Hq, wl.D), float("nan"), dtype=wl.torch_dtype, device="cuda")
             lk.lckv_project_qkv(gc.h, layer, x.cuda(), hidden, dev(wq), dev(wk), dev(wv), q_out, gc.lens, wl.B,
@@ -125,6 +135,9 @@ def test_project_argument_errors():
         assert call(7) == lk.LCKV_ERR_LAYER and call(producers[0], B=3) == lk.LCKV_ERR_BATCH
         assert call(producers[0], wsn=n - 1) == lk.LCKV_ERR_WORKSPACE and call(producers[0], wsp=None) == \
             lk.LCKV_ERR_WORKSPACE
+        pack = lambda rows, hid, dst=ws.data_ptr(): L.lckv_pack_projection_weight(gc.h, p, dst, rows, hid, st)
+        assert pack(24, 256) == lk.LCKV_ERR_CONFIG and pack(32, 128) == lk.LCKV_ERR_CONFIG
+        assert pack(32, 256, dst=p) == lk.LCKV_ERR_CONFIG and pack(32, 256, dst=None) == lk.LCKV_ERR_NULL
         torch.cuda.synchronize()
     with GpuCache(wl, 32, np.array([3, 4], np.int32), sink=4, window=28) as gc:
         shared = [l for l in producers if not lk.lckv_kv_slot(gc.h, l)[1]][0]
@@ -148,7 +161,7 @@ def test_decode_steps_from_hidden_states():
         Kf, Vf = to_f32_numpy(K0), to_f32_numpy(V0)                      # oracle's caches [slot][B][T][Hkv][D]
         producers = {lk.lckv_slot_producer(gc.h, s): s for s in range(ns)}
         W = [weights(wl, hidden, l, l in producers) for l in range(wl.L)]
-        Wd = [[None if t is None else t.cuda() for t in w] for w in W]
+        Wd = [[packed(gc.h, t) for t in w] for w in W]
         ws = torch.empty(lk.lckv_project_workspace_bytes(gc.h, wl.B, hidden), dtype=torch.uint8, device="cuda")
         lens_o = lens.copy()
         for step in range(steps):
