@@ -24,6 +24,9 @@
  * lckv_oracle_project is the q / k / v projection with the rotary position
  * embedding, the step either side of the attention (which layers have K/V
  * projections at all is the pairing table's producer column).
+ * "Parity unpinned": the paper does not restate the rotary embedding, so the
+ * pairing of channels (i with i + D/2) and the base are the Llama convention
+ * taken as a reading; the formula under that reading is pinned.
  * "Parity unpinned": which layer owns the shared cache when the topmost
  * layers are warmup layers (pairing rule 1 vs rule 2 below) is not decided by
  * the paper; both are implemented, rule 1 is the default.
