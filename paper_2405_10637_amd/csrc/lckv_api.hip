@@ -14,6 +14,9 @@ constexpr uint64_t kMagic = 0x4c434b5643414348ull;  // "LCKVCACH"
 constexpr size_t kProfilePairs = 4096;
 constexpr int kTargetWorkgroups = 2048;  // 8 per compute unit: enough to hide the tail of the last wave of groups
 constexpr int kMinSplitTokens = 256;
+constexpr int kMinSplitBytes = 256 * 1024;  // K/V bytes of one kv head a split should at least stream: below that
+                                            // a workgroup is over before its loads are up to speed, and the
+                                            // merge of the partial results costs more than the split gains
 constexpr double kLastLevelCacheBytes = 256.0 * 1024 * 1024;  // MI355X Infinity Cache
 
 bool valid(const lckv_cache *c) { return c && c->magic == kMagic; }
@@ -135,7 +138,9 @@ SplitPlan plan_splits(const lckv_cache *c, int B, int max_n) {
     } else {
         int64_t units = (int64_t)B * c->cfg.Hkv;
         int64_t want = (kTargetWorkgroups + units - 1) / units;
-        int64_t most = max_n / kMinSplitTokens;
+        int64_t min_tokens = kMinSplitBytes / (2 * (int64_t)c->cfg.D * elem_bytes(c->cfg.dtype));
+        if (min_tokens < kMinSplitTokens) min_tokens = kMinSplitTokens;
+        int64_t most = max_n / min_tokens;
         if (most < 1) most = 1;
         if (want > most) want = most;
         if (want < 1) want = 1;

@@ -128,6 +128,12 @@ def test_project_argument_errors():
             gc.h, layer, p, hidden, p, wk, wv, p, gc.lens.data_ptr(), B, 10000.0, wsp, wsn, st)
         producers = [lk.lckv_slot_producer(gc.h, s) for s in range(gc.n_slots)]
         other = [l for l in range(wl.L) if l not in producers][0]
+        # workspace = fp32 partial sums [hidden slices][B][(Hq + 2 Hkv) D]: one slice of 256 channels here,
+        # four at hidden 1024 (512-channel slices are taken only when they still fill the chip)
+        assert n == 1 * 2 * (2 + 2 * 2) * 64 * 4
+        assert lk.lckv_project_workspace_bytes(gc.h, 2, 1024) == 4 * 2 * (2 + 2 * 2) * 64 * 4
+        with pytest.raises(lk.LckvError):
+            lk.lckv_project_workspace_bytes(gc.h, 2, 100)
         assert call(other) == lk.LCKV_ERR_NOT_PRODUCER            # such a layer has no W_K, W_V
         assert call(other, wk=None, wv=None) == lk.LCKV_OK
         assert call(producers[0], wk=None) == lk.LCKV_ERR_NULL and call(producers[0], wv=None) == lk.LCKV_ERR_NULL
