@@ -221,12 +221,18 @@ __global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void pre
             b23 = nv1 >= 4 ? 0xffffffffu : (nv1 == 3 ? 0x0000ffffu : 0u);
         }
         if (!second) b01 = b23 = 0u;  // that LDS page holds nothing of this wave's
+        const bool clear_stale = (pg + 2) * kPage > len || !second;
 #pragma unroll
         for (int dp = 0; dp < D / 32; ++dp) {
             const u32x4 v0 = *(const u32x4 *)(page0 + kPair / 2 + dp * 1024 + lane_off);
             const u32x4 v1 = *(const u32x4 *)(page1 + kPair / 2 + dp * 1024 + lane_off);
-            const u32x4 lo = {v0[0] & a01, v0[1] & a23, v1[0] & b01, v1[1] & b23};  // channel block 2dp, 8 keys
-            const u32x4 hi = {v0[2] & a01, v0[3] & a23, v1[2] & b01, v1[3] & b23};  // channel block 2dp + 1
+            u32x4 lo = {v0[0], v0[1], v1[0], v1[1]};  // channel block 2dp, 8 keys
+            u32x4 hi = {v0[2], v0[3], v1[2], v1[3]};  // channel block 2dp + 1
+            if (clear_stale) {                        // wave-uniform, true only for a wave's last pairs
+                const u32x4 keep = {a01, a23, b01, b23};
+                lo &= keep;
+                hi &= keep;
+            }
 #pragma unroll
             for (int x = 0; x < QB; ++x) {
                 if (!live[x]) continue;
