@@ -14,7 +14,7 @@
 //      q_out / the cache pages
 // The product streams each weight once from HBM (what bounds it: 2 * N * hidden bytes against 4 * B flops per
 // weight) and is shaped for that.  A workgroup of 4 waves owns 128 output features x one slice of KSTEPS * 32
-// hidden channels x up to 128 sequences (in two rounds of 64).  Each wave owns two 16-feature tiles whose weights it loads straight
+// hidden channels x up to 128 sequences (in two rounds of 64, both x slices in LDS from the start).  Each wave owns two 16-feature tiles whose weights it loads straight
 // into registers, all of them issued before anything else (up to 128 KiB per workgroup in flight); meanwhile the
 // x slice is staged in LDS in matrix-operand order, shared by the waves; after one barrier the wave runs its
 // matrix instructions, each LDS read of an x operand feeding two of them.  Features on the rows of the tiles
@@ -93,80 +93,86 @@ __global__ void pack_weight_bf16_kernel(const uint16_t *src, uint16_t *dst, int 
 
 // Launch 1, bf16.  NB = 16-sequence blocks per pass (1, 2, 4 or 8), KSTEPS = matrix instructions (32 hidden
 // channels each) per slice.  grid (feature blocks, slices, passes of 16 * NB sequences).
-template <int NB, int KSTEPS>
-__global__ __launch_bounds__(256, 2) void project_bf16_kernel(ProjParams p, int rounds) {
-    // The x slice in LDS.  With 512-channel slices a sequence's slice is 1 KiB = one fully coalesced load
-    // instruction, so it is kept row-major, rows 1 KiB + 16 bytes apart: lane (kb, c) then reads its operand of
-    // step s at row c, byte 64s + 16kb, and the 16 lanes of a quarter wave fall on 16 different bank quadruples.
-    // With 256-channel slices the image is in operand order (each instruction gathers 64 bytes of 16 sequences).
+template <int NB, int KSTEPS, int ROUNDS>
+__global__ __launch_bounds__(256, (ROUNDS == 1 ? 2 : 1)) void project_bf16_kernel(ProjParams p) {
+    // The x slices in LDS, one buffer per round of 16 * NB sequences.  With 512-channel slices a sequence's slice
+    // is 1 KiB = one fully coalesced load instruction, so it is kept row-major, rows 1 KiB + 16 bytes apart: lane
+    // (kb, c) then reads its operand of step s at row c, byte 64s + 16kb, and the 16 lanes of a quarter wave fall
+    // on 16 different bank quadruples.  With 256-channel slices the image is in operand order (each instruction
+    // gathers 64 bytes of 16 sequences).
     constexpr bool kRowMajor = KSTEPS == 16;
     constexpr int kRowStride = KSTEPS * 64 + 16;
-    __shared__ __attribute__((aligned(16))) char lds[kRowMajor ? NB * 16 * kRowStride : NB * KSTEPS * 1024];
+    constexpr int kRoundBytes = kRowMajor ? NB * 16 * kRowStride : NB * KSTEPS * 1024;
+    constexpr int kDmaPerWave = kRowMajor ? 4 * NB : NB * KSTEPS / 4;  // load instructions per wave and round
+    __shared__ __attribute__((aligned(16))) char lds[ROUNDS * kRoundBytes];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, kb = lane >> 4;
     const int c0 = blockIdx.y * (KSTEPS * 32);
     static_assert(NB * KSTEPS % 4 == 0, "tiles divide among the four waves");
+    static_assert(2 * KSTEPS + (ROUNDS - 1) * kDmaPerWave < 64, "the wait below counts this many loads");
 
-    // this wave's weights: two tiles x KSTEPS steps, from the packed image: every load instruction is one
-    // contiguous, lane-ordered KiB and the KSTEPS loads of a tile are consecutive KiBs
-    u32x4 wr[2][KSTEPS];
-    bool have[2];
+    // 1. The x slices of all rounds into LDS by direct global-to-LDS loads (issued as assembly: the compiler's
+    //    builtin would make every LDS read below wait on each of them separately).  Rows past the batch: the last
+    //    row, whose columns are never stored.
+    auto dma = [&](const uint16_t *src, const char *dst_lds) {  // lane l's 16 bytes land at dst_lds + 16 l
+        const uint32_t dst = (uint32_t)(uintptr_t)(LdsPtr)dst_lds;
+        uint32_t m0_saved;  // M0 carries the LDS address; whatever the compiler keeps there is put back
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
+                     "s_mov_b32 m0, %0"
+                     : "=&s"(m0_saved)
+                     : "s"(dst), "v"(src)
+                     : "memory");
+    };
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int n0 = blockIdx.x * kTileRows + (wave * 2 + nt) * 16;
-        have[nt] = n0 < p.n_total;  // wave-uniform
-        if (have[nt]) {
-            const char *img = stacked_tile(p, n0 >> 4) + ((int64_t)(c0 / 32) * 64 + lane) * 16;
+    for (int round = 0; round < ROUNDS; ++round) {
+        const int b0 = (blockIdx.z * ROUNDS + round) * (16 * NB);
+        const char *buf = lds + round * kRoundBytes;
+        if (kRowMajor) {
 #pragma unroll
-            for (int s = 0; s < KSTEPS; ++s) wr[nt][s] = __builtin_nontemporal_load((const u32x4 *)(img + s * 1024));
+            for (int k = 0; k < kDmaPerWave; ++k) {  // one instruction per sequence
+                const int row = wave + 4 * k;
+                dma((const uint16_t *)p.x + (int64_t)min(b0 + row, p.B - 1) * p.hidden + c0 + lane * 8,
+                    buf + row * kRowStride);
+            }
         } else {
 #pragma unroll
-            for (int s = 0; s < KSTEPS; ++s) wr[nt][s] = u32x4{0u, 0u, 0u, 0u};
+            for (int k = 0; k < kDmaPerWave; ++k) {  // one instruction per (sequence block j, step st) operand
+                const int tile = wave + 4 * k, j = tile / KSTEPS, st = tile % KSTEPS;
+                dma((const uint16_t *)p.x + (int64_t)min(b0 + 16 * j + r, p.B - 1) * p.hidden + c0 + st * 32 + kb * 8,
+                    buf + tile * 1024);
+            }
         }
     }
 
-    // The weights stay in registers while the sequences of this pass go by in rounds of 16 * NB (the x slice of
-    // more would not leave LDS for a second workgroup on the compute unit, and it is the other workgroup that
-    // computes while this one waits for its loads).
-    float *part = p.acc + (int64_t)blockIdx.y * p.B * p.n_total;
-    for (int round = 0; round < rounds; ++round) {
-        const int b0 = (blockIdx.z * rounds + round) * (16 * NB);
-        if (b0 >= p.B) break;  // uniform
-        // The x slice into LDS by direct global-to-LDS loads (issued as assembly: the compiler's builtin would make
-        // every LDS read below wait on each of them separately).  Rows past the batch: the last row, whose columns
-        // are never stored.
-        if (round > 0) asm volatile("s_barrier" ::: "memory");  // everyone has finished reading the last slice
-        auto dma = [&](const uint16_t *src, const char *dst_lds) {  // lane l's 16 bytes land at dst_lds + 16 l
-            const uint32_t dst = (uint32_t)(uintptr_t)(LdsPtr)dst_lds;
-            uint32_t m0_saved;  // M0 carries the LDS address; whatever the compiler keeps there is put back
-            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
-                         "s_mov_b32 m0, %0"
-                         : "=&s"(m0_saved)
-                         : "s"(dst), "v"(src)
-                         : "memory");
-        };
-        if (kRowMajor) {
-            // a sequence's slice is 1 KiB: one instruction per sequence, rows kRowStride apart in LDS
+    // 2. This wave's weights: two tiles x KSTEPS steps, from the packed image: every load instruction is one
+    //    contiguous, lane-ordered KiB and the KSTEPS loads of a tile are consecutive KiBs.  (A tile past the end
+    //    of the matrix reads the last tile instead, so that every wave has the same number of loads in flight.)
+    u32x4 wr[2][KSTEPS];
+    bool have[2];
+    const int last_tile = p.n_total / 16 - 1;
 #pragma unroll
-            for (int k = 0; k < 4 * NB; ++k) {
-                const int row = wave + 4 * k;
-                dma((const uint16_t *)p.x + (int64_t)min(b0 + row, p.B - 1) * p.hidden + c0 + lane * 8,
-                    lds + row * kRowStride);
-            }
-        } else {
-            // operand order [sequence block][step s][lane (kb, b % 16)][8 channels]: one instruction fills the 1 KiB
-            // operand of one (sequence block, step), lane (kb, c) fetching channels c0 + 32s + 8kb .. +7 of sequence
-            // b0 + 16j + c
+    for (int nt = 0; nt < 2; ++nt) {
+        const int t = blockIdx.x * (kTileRows / 16) + wave * 2 + nt;
+        have[nt] = t <= last_tile;  // wave-uniform
+        const char *img = stacked_tile(p, min(t, last_tile)) + ((int64_t)(c0 / 32) * 64 + lane) * 16;
 #pragma unroll
-            for (int k = 0; k < NB * KSTEPS / 4; ++k) {
-                const int tile = wave + 4 * k, j = tile / KSTEPS, st = tile % KSTEPS;
-                dma((const uint16_t *)p.x + (int64_t)min(b0 + 16 * j + r, p.B - 1) * p.hidden + c0 + st * 32 + kb * 8,
-                    lds + tile * 1024);
-            }
-        }
-        asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        for (int s = 0; s < KSTEPS; ++s) wr[nt][s] = __builtin_nontemporal_load((const u32x4 *)(img + s * 1024));
+    }
 
+    // 3. The first round's x has landed when at most the later loads are outstanding (loads complete in order):
+    //    the matrix instructions start on it while the weights are still streaming in - the compiler waits for
+    //    each weight register where it is first used.
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * KSTEPS + (ROUNDS - 1) * kDmaPerWave) : "memory");
+    float *part = p.acc + (int64_t)blockIdx.y * p.B * p.n_total;
+#pragma unroll
+    for (int round = 0; round < ROUNDS; ++round) {
+        const int b0 = (blockIdx.z * ROUNDS + round) * (16 * NB);
+        const char *buf = lds + round * kRoundBytes;
+        if (round > 0) {
+            if (b0 >= p.B) break;  // uniform
+            asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");  // every wave's share of this round's x
+        }
         floatx4 acc[2][NB];
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
@@ -176,8 +182,8 @@ __global__ __launch_bounds__(256, 2) void project_bf16_kernel(ProjParams p, int 
         for (int s = 0; s < KSTEPS; ++s)
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
-                const char *xp = kRowMajor ? lds + (16 * j + r) * kRowStride + (4 * s + kb) * 16
-                                           : lds + ((j * KSTEPS + s) * 64 + lane) * 16;
+                const char *xp = kRowMajor ? buf + (16 * j + r) * kRowStride + (4 * s + kb) * 16
+                                           : buf + ((j * KSTEPS + s) * 64 + lane) * 16;
                 const bf16x8 xb = __builtin_bit_cast(bf16x8, *(const u32x4 *)xp);
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
@@ -337,17 +343,19 @@ hipError_t launch_project(const void *x, int hidden, const void *w_q, const void
         const int ksteps = project_slice_channels(p.n_total, hidden) / 32;
         p.n_slices = hidden / (ksteps * 32);
         dim3 grid((p.n_total + kTileRows - 1) / kTileRows, p.n_slices, (B + per_round * rounds - 1) / (per_round * rounds));
-#define LCKV_PROJECT_LAUNCH(NB)                                                                    \
-    if (ksteps == 16)                                                                              \
-        hipLaunchKernelGGL((project_bf16_kernel<NB, 16>), grid, dim3(256), 0, s, p, rounds);       \
-    else                                                                                           \
-        hipLaunchKernelGGL((project_bf16_kernel<NB, 8>), grid, dim3(256), 0, s, p, rounds)
-        if (per_round == 64) {
-            LCKV_PROJECT_LAUNCH(4);
+#define LCKV_PROJECT_LAUNCH(NB, ROUNDS)                                                   \
+    if (ksteps == 16)                                                                     \
+        hipLaunchKernelGGL((project_bf16_kernel<NB, 16, ROUNDS>), grid, dim3(256), 0, s, p); \
+    else                                                                                  \
+        hipLaunchKernelGGL((project_bf16_kernel<NB, 8, ROUNDS>), grid, dim3(256), 0, s, p)
+        if (rounds == 2) {
+            LCKV_PROJECT_LAUNCH(4, 2);
+        } else if (per_round == 64) {
+            LCKV_PROJECT_LAUNCH(4, 1);
         } else if (per_round == 32) {
-            LCKV_PROJECT_LAUNCH(2);
+            LCKV_PROJECT_LAUNCH(2, 1);
         } else {
-            LCKV_PROJECT_LAUNCH(1);
+            LCKV_PROJECT_LAUNCH(1, 1);
         }
 #undef LCKV_PROJECT_LAUNCH
     } else {
