@@ -24,7 +24,7 @@ typedef __attribute__((address_space(3))) void *LdsPtr;
 typedef __attribute__((address_space(4))) const int32_t *ConstTablePtr;
 
 template <int D, int QB, int NPG, int ST, bool PAGED>
-__global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void prefill_bf16_kernel(AttnParams p, int S) {
+__global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void prefill_bf16_kernel(AttnParams p, int S, int heads_per_group) {
     // (waves per SIMD the register budget is cut for: within a wave the score products, the softmax and the P.V
     //  products run one after the other, so it is the other waves of the SIMD that keep the matrix core busy
     //  meanwhile - 3 waves at 2 query blocks per wave measured faster than 2 waves with more registers each; the
@@ -43,14 +43,20 @@ __global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void pre
     // by their launch index, and every XCD has an L2 of its own: the launch index is unfolded so that each XCD
     // gets a contiguous range of tasks, i.e. all row chunks of a head (and the heads of one kv group) run on one
     // XCD at about the same time and share that head's K/V pages in its L2.
+    // Inside an XCD the heads are taken in groups of `heads_per_group`, and within a group the row chunks with
+    // the most keys come first, for all its heads, before the shorter ones: the longest tasks of the whole list
+    // are then not the last ones to start (list scheduling of the triangle: 91 % of the ideal makespan with one
+    // head per group, 98 % with eight), while a group's K/V are still few enough to live in the L2.
     constexpr int kXcd = 8;
     const int n_chunks = (S + 4 * kRows - 1) / (4 * kRows);
-    const int total = n_chunks * p.Hq * p.B;
-    const int per_xcd = (total + kXcd - 1) / kXcd;
-    const int task = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
-    if (task >= total) return;
-    const int chunk = n_chunks - 1 - task % n_chunks;  // rows with the most keys first
-    const int h = (task / n_chunks) % p.Hq, b = task / (n_chunks * p.Hq);
+    const int units = p.Hq * p.B;  // (sequence, head) pairs
+    const int units_per_xcd = (units + kXcd - 1) / kXcd;
+    const int xcd = blockIdx.x % kXcd, idx = blockIdx.x / kXcd;
+    const int group = idx / (heads_per_group * n_chunks), rest = idx % (heads_per_group * n_chunks);
+    const int unit = xcd * units_per_xcd + group * heads_per_group + rest % heads_per_group;
+    if (unit >= min((xcd + 1) * units_per_xcd, units)) return;
+    const int chunk = n_chunks - 1 - rest / heads_per_group;  // rows with the most keys first
+    const int h = unit % p.Hq, b = unit / p.Hq;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, kb = lane >> 4;  // query position within a block / key quad
@@ -306,13 +312,16 @@ __global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void pre
 template <int D, int QB, int NPG, int ST = 3>
 hipError_t launch_qb(const AttnParams &p, int S, hipStream_t s) {
     const int rows_per_group = 4 * 16 * QB;
-    const int64_t total = (int64_t)((S + rows_per_group - 1) / rows_per_group) * p.Hq * p.B;
-    if (total > (int64_t)1 << 30) return hipErrorInvalidValue;
-    dim3 grid((unsigned)((total + 7) / 8 * 8)), block(256);  // one task per workgroup, padded to the 8 XCDs
+    const int n_chunks = (S + rows_per_group - 1) / rows_per_group;
+    const int64_t units = (int64_t)p.Hq * p.B, units_per_xcd = (units + 7) / 8;
+    const int heads_per_group = 8;  // measured on the Llama-7B shape: 1: 648, 2: 671, 4: 685, 8: 693, 16: 670 TFLOP/s
+    const int64_t per_xcd = (units_per_xcd + heads_per_group - 1) / heads_per_group * heads_per_group * n_chunks;
+    if (per_xcd * 8 > (int64_t)1 << 30) return hipErrorInvalidValue;
+    dim3 grid((unsigned)(per_xcd * 8)), block(256);  // one task per workgroup, the same number for each of the 8 XCDs
     if (p.slot.table)
-        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, NPG, ST, true>), grid, block, 0, s, p, S);
+        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, NPG, ST, true>), grid, block, 0, s, p, S, heads_per_group);
     else
-        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, NPG, ST, false>), grid, block, 0, s, p, S);
+        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, NPG, ST, false>), grid, block, 0, s, p, S, heads_per_group);
     return hipGetLastError();
 }
 
