@@ -205,3 +205,56 @@ def test_decode_steps_from_hidden_states():
             gc.lens += 1
             lens_o += 1
         assert gc.device_error() == 0
+
+
+def test_projection_attention_and_prompt_encoding_replay_from_a_hip_graph():
+    # The entry points only enqueue, so a caller may capture them: one layer's projection (+ fused append) and
+    # attention of a decode step, and a prompt-encoding pass, captured once and replayed with new inputs in the
+    # static buffers; every replay is compared with the same calls made eagerly on a twin cache, with eager work
+    # and a synchronisation between the replays.  Results are bitwise equal (fixed order of the partial sums).
+    wl = synth.Workload("pr-graph", "bf16", L=3, w=1, Hq=4, Hkv=2, D=64, B=5, T=40, sigma=1.0, seed=70, warm=(0,))
+    hidden, S = 256, 40
+    lens = np.array([7, 0, 33, 16, 36], np.int32)                       # + 3 bumps stays within the S = 40 prompt rows
+    with GpuCache(wl, 48, lens) as eager, GpuCache(wl, 48, lens) as graphed:
+        K0, V0 = synth.logical_cache(wl, eager.n_slots, 48)
+        for gc in (eager, graphed):
+            for s in range(gc.n_slots):
+                gc.load_dense(s, K0[s], V0[s])
+        layer = lk.lckv_slot_producer(eager.h, eager.n_slots - 1)        # the condensed layer that owns the shared slot
+        W = weights(wl, hidden, layer, True)
+        Wp = {id(gc): [packed(gc.h, w) for w in W] for gc in (eager, graphed)}
+        ws = {id(gc): torch.empty(lk.lckv_project_workspace_bytes(gc.h, wl.B, hidden), dtype=torch.uint8, device="cuda")
+              for gc in (eager, graphed)}
+        aws = {id(gc): gc.workspace(48) for gc in (eager, graphed)}
+        sx = torch.zeros((wl.B, hidden), dtype=torch.bfloat16, device="cuda")            # static buffers of the graph
+        sq = torch.zeros((wl.B, wl.Hq, wl.D), dtype=torch.bfloat16, device="cuda")
+        sout = torch.zeros_like(sq)
+        spq = torch.zeros((wl.B, S, wl.Hq, wl.D), dtype=torch.bfloat16, device="cuda")
+        spout = torch.zeros_like(spq)
+
+        def calls(gc, x, q, out, pq, pout):
+            w = Wp[id(gc)]
+            lk.lckv_project_qkv(gc.h, layer, x, hidden, w[0], w[1], w[2], q, gc.lens, wl.B, 10000.0, ws[id(gc)])
+            lk.lckv_decode_attention(gc.h, layer, q, out, gc.lens, None, wl.B, 47, workspace=aws[id(gc)])
+            lk.lckv_prefill_attention(gc.h, layer, pq, pout, gc.lens, wl.B, S)
+
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            calls(graphed, sx, sq, sout, spq, spout)
+        for rep in range(4):
+            x = synth._normal((wl.B, hidden), 1.0, torch.bfloat16, 7000 + rep).cuda()
+            pq = synth._normal((wl.B, S, wl.Hq, wl.D), 1.0, torch.bfloat16, 7100 + rep).cuda()
+            sx.copy_(x)
+            spq.copy_(pq)
+            g.replay()
+            q = torch.empty_like(sq)
+            out = torch.empty_like(sq)
+            pout = torch.empty_like(spq)
+            calls(eager, x, q, out, pq, pout)
+            torch.cuda.synchronize()
+            assert torch.equal(sq, q) and torch.equal(sout, out) and torch.equal(spout, pout), "replay %d" % rep
+            assert torch.equal(graphed.storage, eager.storage), "the appended K/V differ in replay %d" % rep
+            graphed.lens += 1                                            # eager work between the replays
+            eager.lens += 1
+        assert graphed.device_error() == 0 and eager.device_error() == 0
