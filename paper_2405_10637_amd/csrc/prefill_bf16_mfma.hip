@@ -64,7 +64,22 @@ __global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void pre
     const int i_wg = chunk * 4 * kRows;       // first row of the workgroup
     const int i_lo = i_wg + wave * kRows;     // first row of this wave
 
-    int len = p.seq_lens[b];
+    // Q^T operands first: their addresses need nothing that is loaded, so they travel while the prompt length
+    // and the first tiles are fetched (rows past the prompt are read too - they exist - and not used); they are
+    // waited for just before the loop.
+    bf16x8 qb[QB][D / 32];
+#pragma unroll
+    for (int x = 0; x < QB; ++x) {
+        const int i = i_lo + 16 * x + c;
+        const char *qp = (const char *)p.q + ((((int64_t)b * S + i) * p.Hq + h) * D + kb * 8) * 2;
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ++ks) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (i < S) v = *(const u32x4 *)(qp + ks * 64);
+            qb[x][ks] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+    int len = ((ConstTablePtr)p.seq_lens)[b];  // a scalar load (the lengths are not written while the kernel runs)
     if (len > p.max_n) {
         len = p.max_n;
         if (tid == 0) atomicOr(p.dev_err, LCKV_DEV_ERR_CAPACITY);
@@ -82,7 +97,6 @@ __global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void pre
     }
     if (i_wg >= len) return;  // uniform over the workgroup: nothing to attend
 
-    bf16x8 qb[QB][D / 32];  // Q^T operands (loaded below, behind the first tiles' loads)
     int n_col[QB];          // the number of keys each column sees
 #pragma unroll
     for (int x = 0; x < QB; ++x) n_col[x] = min(i_lo + 16 * x + c + self, len);
@@ -256,19 +270,8 @@ __global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void pre
     // later tiles have" means tile t is there) and every wave has finished reading tile t-1, whose buffer the
     // loads of tile t+ST-1 then overwrite.
     for (int t = 0; t < ST - 1 && t < n_tiles; ++t) issue_tile(t);
-    // Q^T operands, loaded behind the first tiles and waited for here, before the loop: a wait for them inside
-    // the loop would be a wait for all loads in flight.
-#pragma unroll
-    for (int x = 0; x < QB; ++x) {
-        const int i = i_lo + 16 * x + c;
-        const char *qp = (const char *)p.q + ((((int64_t)b * S + i) * p.Hq + h) * D + kb * 8) * 2;
-#pragma unroll
-        for (int ks = 0; ks < D / 32; ++ks) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (active && i < S) v = *(const u32x4 *)(qp + ks * 64);
-            qb[x][ks] = __builtin_bit_cast(bf16x8, v);
-        }
-    }
+    // The Q^T operands are waited for here, before the loop: a wait for them inside the loop would be a wait for
+    // all loads in flight.
 #pragma unroll
     for (int x = 0; x < QB; ++x)
 #pragma unroll
