@@ -168,13 +168,13 @@ int lckv_set_prefill_tile(lckv_cache *cache, int32_t query_blocks_per_wave);
  * caches; the hidden dimension is cut into slices whose partial sums are added in a fixed order, so results do
  * not vary from run to run) or in fp64 (fp32 caches), rotated in fp32 and rounded once to the element type.
  * x: device [B][hidden] in the cache's element type; w_q (Hq*D rows), w_k, w_v (Hkv*D rows): device, PACKED by
- * lckv_pack_projection_weight, 16-byte aligned; bf16 needs hidden % 256 == 0.  w_k and w_v must both be given for a producing
- * layer (LCKV_ERR_NULL) and must both be NULL for any other (LCKV_ERR_NOT_PRODUCER: such parameters do not
- * exist).  q_out: device [B][Hq][D].  dev_seq_lens: read, not changed.  workspace: device, 256-byte aligned,
- * at least lckv_project_workspace_bytes; its contents need not be kept between calls.  With the sink + window
- * policy the condensed producing layer is refused (LCKV_ERR_CONFIG): there its K/V must be stored after the
- * layer's own attention (see lckv_append_kv), so project into buffers of your own with a non-producing call
- * pattern or use lckv_step.  Only enqueues (two launches). */
+ * lckv_pack_projection_weight, 16-byte aligned; bf16 needs hidden % 256 == 0.  w_k and w_v must both be given
+ * for a producing layer (LCKV_ERR_NULL) and must both be NULL for any other (LCKV_ERR_NOT_PRODUCER: such
+ * parameters do not exist).  q_out: device [B][Hq][D].  dev_seq_lens: read, not changed.  workspace: device,
+ * 256-byte aligned, at least lckv_project_workspace_bytes; its contents need not be kept between calls.  With
+ * the sink + window policy the condensed producing layer is refused (LCKV_ERR_CONFIG): there the new K/V must
+ * be stored after the layer's own attention (see lckv_append_kv), which a call that stores them at once
+ * cannot honour.  Only enqueues (two launches). */
 int lckv_project_qkv(lckv_cache *cache, int32_t layer, const void *x, int32_t hidden, const void *w_q,
                      const void *w_k, const void *w_v, void *q_out, const int32_t *dev_seq_lens, int32_t B,
                      float rope_base, void *workspace, size_t workspace_bytes, void *hip_stream);
