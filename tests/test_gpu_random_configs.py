@@ -69,3 +69,16 @@ def test_projection_random_config(seed):
     top = 40
     lens = np.minimum(random_lens(rng, wl.B, top), top - 1)      # the new token needs a free position
     run_project(wl.with_(T=top), hidden, lens, 48, rope_base=float(rng.choice([10000.0, 500000.0, 0.0])))
+
+
+@pytest.mark.parametrize("seed", range(8 * MORE))
+def test_sink_window_policy_random_config(seed):
+    from test_gpu_streaming import run_streaming
+    rng = np.random.default_rng(9300 + seed)
+    wl = random_workload(rng, "rnd-stream-%d" % seed, max_B=4)
+    sink = int(rng.choice([0, 1, 4, 7]))
+    window = int(rng.choice([9, 16, 23, 40]))
+    lens0 = np.minimum(random_lens(rng, wl.B, sink + window), sink + window)
+    steps = int(rng.integers(window + 2, 3 * window))               # past the capacity: the ring wraps
+    run_streaming(wl.with_(T=sink + window), sink, window, lens0, steps, rule=int(rng.integers(0, 2)),
+                  split_tokens=int(rng.choice([0, 16])))
