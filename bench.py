@@ -182,7 +182,7 @@ def prefill_bench(steps, warmup, tile):
             "max_abs_err_vs_oracle": err, "max_abs_expected": ref}))
 
 
-def project_bench(steps, warmup, batch):
+def project_bench(steps, warmup, batch, graph=False):
     """The projections of one decode step (lckv_project_qkv for every layer: queries everywhere, keys and values
     - rotated and stored into the cache - for the producing layers only), Llama-7B shape, bf16, hidden 4096.
     Weight-streaming bound: reported against the HBM peak.  Checks sampled outputs against the oracle.
@@ -234,13 +234,20 @@ def project_bench(steps, warmup, batch):
                     err, ref = max(err, float(np.abs(got - want[0, 0]).max())), max(ref, float(np.abs(want).max()))
         if err > 2e-2 or err > 1e-2 * max(ref, 1e-3):
             sys.exit("projection disagrees with the oracle: err %g, max expected %g" % (err, ref))
+        run = one_step
+        if graph:                                    # the 64 launches of a step captured once, replayed per step
+            torch.cuda.synchronize()
+            g_ = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_):
+                one_step()
+            run = g_.replay
         for _ in range(warmup):
-            one_step()
+            run()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
         for _ in range(steps):
-            one_step()
+            run()
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / steps
@@ -252,8 +259,9 @@ def project_bench(steps, warmup, batch):
             "metric": "q/k/v projections + rotary embedding + append of one decode step (Llama-7B shape, B=%d)" % batch,
             "value": wl.B / (ms * 1e-3), "unit": "tokens/s (projections only)", "n_gpus": 1, "steps": steps,
             "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+            "launch": "graph replay" if graph else "eager",
             "config": {"workload": wl.name, "hidden": hidden, "producing_layers": sorted(producers)},
-            "roofline": {"bound": "hbm", "kernel": "project_bf16_kernel (+ prepare, finish)", "achieved": gbps,
+            "roofline": {"bound": "hbm", "kernel": "project_bf16_kernel (+ finish)", "achieved": gbps,
                          "peak": 8000.0, "unit": "GB/s", "frac": gbps / 8000.0, "traffic": None},
             "weight_rows_streamed": rows, "weight_rows_with_kv_everywhere": full,
             "max_abs_err_vs_oracle": err, "max_abs_expected": ref}))
@@ -293,7 +301,7 @@ def main():
     if args.prefill:
         return prefill_bench(args.steps, args.warmup, args.prefill_tile)
     if args.project:
-        return project_bench(args.steps, args.warmup, args.batch)
+        return project_bench(args.steps, args.warmup, args.batch, args.graph)
 
     import numpy as np
     import torch
