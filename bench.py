@@ -24,6 +24,17 @@ METRIC = {
 }
 
 
+def key_visits_per_step(lens, self_visible, Hq, step_index=0):
+    """(query head, key) pairs one decode step evaluates: every layer l, sequence b and query head attends to
+    lens[b] + step_index keys, plus the token itself in a warmup layer (Section 2.1).  The CPU oracle's sample is
+    counted in the same unit (keys per (layer, sequence, query head) item), so sample time scales by the ratio."""
+    total = 0
+    for vis in self_visible:
+        for n in lens:
+            total += (int(n) + step_index + (1 if vis else 0)) * Hq
+    return total
+
+
 def cpu_baseline(sess, units, kv, q, k_new, v_new, out, target_cpu_s=12.0):
     """Time the CPU oracle (as it stands) on a bounded sample of (layer, b, head) units of this workload, check the
     GPU's output for those units against it, and extrapolate the sample's time to a whole step."""
@@ -65,13 +76,13 @@ def cpu_baseline(sess, units, kv, q, k_new, v_new, out, target_cpu_s=12.0):
     got = np.stack([out[l, b, h].float().cpu().numpy() for (l, b, h) in units]).astype(np.float64)
     err = float(np.abs(got - want).max())
     ref = float(np.abs(want).max())
-    total_visits = sess.kv_bytes_per_step(0) // (2 * wl.Hkv * wl.D * wl.elem_bytes) * G   # (query head, key) pairs
+    total_visits = key_visits_per_step(sess.lens0, [vis for (_, vis) in sess.kv_slot], wl.Hq)
     step_s = dt * (total_visits / float(nk.sum()))
     return {
         "value": wl.B / step_s, "unit": "tokens/s", "cores": threads, "kind": "oracle",
         "sample": "%d of %d (layer, sequence, head) units of the same step, best of %d runs (%.1f core-seconds "
-                  "in all), time scaled by key visits (%.3g s for the sample)"
-                  % (N, wl.L * wl.B * wl.Hq, reps, spent * threads, dt),
+                  "in all), time scaled by (query head, key) visits: %d in the sample, %d in the step (%.3g s for "
+                  "the sample)" % (N, wl.L * wl.B * wl.Hq, reps, spent * threads, int(nk.sum()), total_visits, dt),
         "max_abs_err_vs_gpu": err, "max_abs_expected": ref,
     }
 
