@@ -17,6 +17,10 @@
  *     lckv_cache_alloc, so it may be captured into a HIP graph.
  *   - Tensors are dense, row-major, in the cache's element type (bf16 or fp32), 16-byte aligned.
  *   - Sequence lengths live on the device (int32[B]): t_b = tokens already cached for sequence b.
+ *   - On a host without a GPU lckv_cache_alloc still returns a handle: the pairing table, the planners and every
+ *     argument check work on it, and each call that would enqueue work returns LCKV_ERR_HIP after its checks.
+ *   - Measurement and tuning hooks (kernel timing, read probe, forced split size, load policy, prefill tile) are
+ *     declared in lckv_tools.h, not here.
  *
  * Physical cache layout (private to the library, stated so that storage can be sized and reasoned about):
  * a slot is an array of "page pairs"; a page pair holds 16 consecutive positions of one kv head, first the K
@@ -109,7 +113,8 @@ int lckv_cache_free(lckv_cache *cache);
 /* Paged caches: device table int32[B_max][max_blocks_per_seq]; entry [b][p] is the physical block holding
  * positions 16p..16p+15 of sequence b in EVERY slot (one table serves all slots).  Borrowed, not copied: it
  * must stay valid, and may be updated by the caller between calls.  Capacity per sequence becomes
- * 16 * max_blocks_per_seq. */
+ * 16 * max_blocks_per_seq; with the sink + window policy a row must hold sink_tokens + window_tokens positions
+ * (LCKV_ERR_BLOCK_TABLE otherwise, here and in every call that would index such a row). */
 int lckv_cache_set_block_table(lckv_cache *cache, const int32_t *dev_table, int32_t max_blocks_per_seq);
 
 /* Pairing table (Section 2.1): number of slots; the slot layer `layer` reads and whether the token being
@@ -119,7 +124,9 @@ int lckv_n_slots(const lckv_cache *cache, int32_t *n_slots);
 int lckv_kv_slot(const lckv_cache *cache, int32_t layer, int32_t *slot, int32_t *self_visible);
 int lckv_slot_producer(const lckv_cache *cache, int32_t slot, int32_t *layer);
 
-/* Store the new token's K/V of a producing layer: for every b < B,
+/* Store the new token's K/V of a producing layer (Section 2.1: only the K/V of the top layer - and of the warmup
+ * layers, which keep standard attention - are computed and cached; Section 3.3 for where the new token goes and
+ * when under the sink + window policy): for every b < B,
  *   K[slot(layer)][b][t_b] = k_new[b], V[...] = v_new[b]      (bits copied unchanged)
  * k_new, v_new: device [B][Hkv][D].  dev_seq_lens: device int32[B], read, not changed.
  * A sequence already at capacity is skipped and LCKV_DEV_ERR_CAPACITY is raised on the device (never with the
@@ -150,18 +157,24 @@ int lckv_decode_attention(lckv_cache *cache, int32_t layer, const void *q, void 
  * the caller first imports them with lckv_cache_load_dense - a warmup layer's own K/V of this iteration before
  * its attention, the top layer's K/V into the shared slot at the END of an iteration - so after the last
  * iteration the cache holds the prompt and decoding can start.  q, out: device [B][S][Hq][D]; dev_prompt_lens:
- * device int32[B], each <= S; S <= capacity.  Not available with the sink + window policy.  Only enqueues. */
+ * device int32[B], each <= S; S <= capacity.  Not available with the sink + window policy.  Only enqueues.
+ * The bf16 kernel's workgroup-to-task map is laid out for MI355X's 8 XCDs with round-robin dispatch of
+ * workgroups (all row chunks of a head on one XCD, sharing its L2); on another partitioning the results are the
+ * same and only the cache reuse changes. */
 int lckv_prefill_attention(lckv_cache *cache, int32_t layer, const void *q, void *out,
                            const int32_t *dev_prompt_lens, int32_t B, int32_t S, void *hip_stream);
-/* Tuning knob of the bf16 prefill kernel: 16-position query blocks per wave, 2 or 4 (0 = default).  Host only. */
-int lckv_set_prefill_tile(lckv_cache *cache, int32_t query_blocks_per_wave);
 
 /* The projections either side of the attention for one decode step of `layer` (Section 2.1: every layer maps
  * the hidden state to queries, but only a layer that produces a cache slot - a warmup layer, or the condensed
  * layer that owns the shared cache - computes keys and values; the other layers have no W_K, W_V):
  *   q_out[b] = rot_{t_b}(x[b] . w_q^T)                                    every layer
  *   K[slot][b][t_b] = rot_{t_b}(x[b] . w_k^T),  V[slot][b][t_b] = x[b] . w_v^T    producing layers only
- * i.e. for a producing layer the call also performs lckv_append_kv of the new token, straight from the product.
+ * i.e. for a producing layer the call also performs lckv_append_kv of the new token, straight from the product -
+ * unless k_out and v_out (device [B][Hkv][D], both or neither) are given: then the rotated keys and the values go
+ * there instead, the cache is not touched, and the caller stores them with lckv_append_kv when the time has come.
+ * That is how the condensed producing layer is driven under the sink + window policy (Section 3.3), where its new
+ * K/V may only replace a ring entry after the layer's own attention; storing at once is refused there
+ * (LCKV_ERR_CONFIG).
  * rot_t is the rotary position embedding in the Llama convention (the paper trains Llama models and does not
  * restate it): within a head, channel i < D/2 is paired with channel i + D/2 and the pair is turned by the
  * angle t * rope_base^(-2i/D); rope_base <= 0 means no rotation.  Products are accumulated in fp32 (bf16
@@ -171,13 +184,12 @@ int lckv_set_prefill_tile(lckv_cache *cache, int32_t query_blocks_per_wave);
  * lckv_pack_projection_weight, 16-byte aligned; bf16 needs hidden % 256 == 0.  w_k and w_v must both be given
  * for a producing layer (LCKV_ERR_NULL) and must both be NULL for any other (LCKV_ERR_NOT_PRODUCER: such
  * parameters do not exist).  q_out: device [B][Hq][D].  dev_seq_lens: read, not changed.  workspace: device,
- * 256-byte aligned, at least lckv_project_workspace_bytes; its contents need not be kept between calls.  With
- * the sink + window policy the condensed producing layer is refused (LCKV_ERR_CONFIG): there the new K/V must
- * be stored after the layer's own attention (see lckv_append_kv), which a call that stores them at once
- * cannot honour.  Only enqueues (two launches). */
+ * 256-byte aligned, at least lckv_project_workspace_bytes; its contents need not be kept between calls.
+ * k_out / v_out on a layer that produces no slot: LCKV_ERR_NOT_PRODUCER.  Only enqueues. */
 int lckv_project_qkv(lckv_cache *cache, int32_t layer, const void *x, int32_t hidden, const void *w_q,
-                     const void *w_k, const void *w_v, void *q_out, const int32_t *dev_seq_lens, int32_t B,
-                     float rope_base, void *workspace, size_t workspace_bytes, void *hip_stream);
+                     const void *w_k, const void *w_v, void *q_out, void *k_out, void *v_out,
+                     const int32_t *dev_seq_lens, int32_t B, float rope_base, void *workspace,
+                     size_t workspace_bytes, void *hip_stream);
 int lckv_project_workspace_bytes(const lckv_cache *cache, int32_t B, int32_t hidden, size_t *bytes);
 /* Weights are handed to lckv_project_qkv in the order the matrix instructions take them (made once, when the
  * model is loaded).  w: device [n_rows][hidden] row-major ("out features x in features"), n_rows % 16 == 0;
@@ -187,8 +199,9 @@ int lckv_project_workspace_bytes(const lckv_cache *cache, int32_t B, int32_t hid
 int lckv_pack_projection_weight(const lckv_cache *cache, const void *w, void *w_packed, int32_t n_rows,
                                 int32_t hidden, void *hip_stream);
 
-/* The whole step: layers in index order (layer l+1 starts after layer l has finished: in the model its query
- * depends on layer l's output); a warmup layer's K/V are appended just before its attention (it sees itself),
+/* The whole decode step of Section 2.1 (Figure 1b) for one new token per sequence: layers in index order (layer
+ * l+1 starts after layer l has finished: in the model its query depends on layer l's output, the "bottom-up
+ * computation" of that section); a warmup layer's K/V are appended just before its attention (it sees itself),
  * the shared slot's new K/V just after the attention of the condensed layer that produces them (the diagonal is
  * masked, so no condensed layer sees them in this step); at the end every t_b is incremented on the device.
  * With the sink + window policy max_len_hint may exceed the capacity.
@@ -200,21 +213,10 @@ int lckv_step(lckv_cache *cache, const void *q_all, const void *k_new_all, const
 /* Bytes of workspace lckv_decode_attention / lckv_step need for this B and max_len_hint.  Host only. */
 int lckv_workspace_bytes(const lckv_cache *cache, int32_t B, int32_t max_len_hint, size_t *bytes);
 
-/* Force the number of keys per split (a multiple of 16; 0 = choose from B, Hkv and max_len_hint).  The split
- * of a sequence's keys never depends on other sequences' lengths.  Host only; meant for tests and tuning. */
-int lckv_set_split_tokens(lckv_cache *cache, int32_t tokens);
-
-/* How the attention kernels read K/V: AUTO uses the nontemporal hint when one layer's pass over its slot is
- * larger than the 256 MB last-level cache (nothing of it would survive until the next layer's pass), plain loads
- * otherwise (a small shared slot is re-read by every condensed layer and may stay cached).  Host only. */
-#define LCKV_LOAD_AUTO 0
-#define LCKV_LOAD_TEMPORAL 1
-#define LCKV_LOAD_NONTEMPORAL 2
-int lckv_set_load_policy(lckv_cache *cache, int32_t policy);
-
 /* Bulk import (e.g. after prompt encoding): positions [0, min(T, t_b)) of every sequence b < B of `slot` are
  * written from dense device tensors k, v of shape [B][T][Hkv][D]; dev_seq_lens (device int32[B]) may be NULL,
- * then all T positions are written.  Bits copied unchanged. */
+ * then all T positions are written.  Bits copied unchanged.  This is the store of Section 2.3's prompt encoding:
+ * each of its m + b iterations imports a producing layer's K/V of all prompt tokens before the next reads them. */
 int lckv_cache_load_dense(lckv_cache *cache, int32_t slot, const void *k, const void *v,
                           const int32_t *dev_seq_lens, int32_t B, int32_t T, void *hip_stream);
 
@@ -225,21 +227,6 @@ int lckv_cache_read(lckv_cache *cache, int32_t slot, int32_t b, int32_t pos, int
 
 /* Read and clear the sticky device error bits (LCKV_DEV_ERR_*).  SYNCHRONISES the device. */
 int lckv_last_device_error(lckv_cache *cache, int32_t *bits);
-
-/* Kernel timing for benchmarks: while enabled, every attention kernel launch is bracketed by HIP events on
- * its stream (do not enable during graph capture).  lckv_profile_read SYNCHRONISES, returns the number of
- * timed launches and their summed duration since the last read, and resets both. */
-int lckv_profile_enable(lckv_cache *cache, int32_t enable);
-int lckv_profile_read(lckv_cache *cache, int32_t *n_launches, double *total_ms);
-/* The individual durations (milliseconds, launch order) of the launches timed since the last lckv_profile_read:
- * up to `capacity` of them are written to host array `ms`, *n_launches gets their number.  SYNCHRONISES; does not
- * reset (call it before lckv_profile_read). */
-int lckv_profile_launch_ms(lckv_cache *cache, float *ms, int32_t capacity, int32_t *n_launches);
-
-/* Measurement aid: read `bytes` (a multiple of 2 MiB is read, the rest ignored) of device memory with the
- * attention kernel's load pattern (with or without the nontemporal hint) and discard them; timing it gives the
- * read bandwidth reachable on the device at hand, to set beside the published peak.  Only enqueues. */
-int lckv_hbm_read_probe(lckv_cache *cache, const void *dev_buf, size_t bytes, int32_t nontemporal, void *hip_stream);
 
 const char *lckv_strerror(int code);
 

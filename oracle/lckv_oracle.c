@@ -24,6 +24,10 @@
  * lckv_oracle_project is the q / k / v projection with the rotary position
  * embedding, the step either side of the attention (which layers have K/V
  * projections at all is the pairing table's producer column).
+ * lckv_oracle_footprint / lckv_oracle_max_batch are the memory side of the
+ * method (Sections 1 and 3.1): bytes of K and V kept for a batch, counted
+ * cache by cache from the pairing table, and the largest batch under a byte
+ * budget found by trying batch sizes upward.
  * "Parity unpinned": the paper does not restate the rotary embedding, so the
  * pairing of channels (i with i + D/2) and the base are the Llama convention
  * taken as a reading; the formula under that reading is pinned.
@@ -383,6 +387,55 @@ int lckv_oracle_project(int B, int hidden, int n_heads, int D, const float *x,
         }
     }
     return 0;
+}
+
+/*
+ * Bytes of KV cache for B sequences of T positions (Section 1: the KV cache
+ * grows with the sequence length and with the number of layers that keep
+ * one; Section 2.1: here only the top layer and the warmup layers keep one).
+ * Counted the long way: every cache named by the pairing table holds, per
+ * sequence and position, one key and one value of D elements for each of its
+ * Hkv heads.  Returns -1 on a bad argument.
+ */
+int64_t lckv_oracle_footprint(int L, const uint8_t *warm, int rule, int64_t B,
+                              int64_t T, int Hkv, int D, int elem_bytes)
+{
+    if (L <= 0 || B < 0 || T < 0 || Hkv <= 0 || D <= 0 || elem_bytes <= 0)
+        return -1;
+    int32_t *kv_slot = (int32_t *)malloc(sizeof(int32_t) * (size_t)L * 3);
+    if (!kv_slot) return -1;
+    int32_t n_slots = 0;
+    if (lckv_oracle_pairing(L, warm, rule, kv_slot, kv_slot + L, kv_slot + 2 * L,
+                            &n_slots) != 0) {
+        free(kv_slot);
+        return -1;
+    }
+    free(kv_slot);
+    int64_t bytes = 0;
+    for (int s = 0; s < n_slots; ++s)          /* every cache that is kept    */
+        for (int64_t b = 0; b < B; ++b)        /* every sequence              */
+            bytes += T * (int64_t)Hkv * D * elem_bytes   /* its keys          */
+                   + T * (int64_t)Hkv * D * elem_bytes;  /* and its values    */
+    return bytes;
+}
+
+/*
+ * The largest batch whose caches fit in `budget` bytes (Section 3.1: the
+ * maximum batch size is what the memory allows), found by trying batch sizes
+ * upward; at most `limit` sequences.  Returns -1 on a bad argument.
+ */
+int64_t lckv_oracle_max_batch(int L, const uint8_t *warm, int rule, int64_t T,
+                              int Hkv, int D, int elem_bytes, int64_t budget,
+                              int64_t limit)
+{
+    if (budget < 0 || limit < 0) return -1;
+    if (lckv_oracle_footprint(L, warm, rule, 0, T, Hkv, D, elem_bytes) < 0)
+        return -1;
+    int64_t B = 0;
+    while (B < limit &&
+           lckv_oracle_footprint(L, warm, rule, B + 1, T, Hkv, D, elem_bytes) <= budget)
+        ++B;
+    return B;
 }
 
 int lckv_oracle_max_threads(void)

@@ -76,6 +76,12 @@ def _load():
         lib.lckv_oracle_prefill_attention.restype = ctypes.c_int
         lib.lckv_oracle_project.argtypes = [ctypes.c_int] * 4 + [f32p, f32p, i64p, ctypes.c_double, f64p]
         lib.lckv_oracle_project.restype = ctypes.c_int
+        lib.lckv_oracle_footprint.argtypes = [ctypes.c_int, u8p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                              ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.lckv_oracle_footprint.restype = ctypes.c_int64
+        lib.lckv_oracle_max_batch.argtypes = [ctypes.c_int, u8p, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
+                                              ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64]
+        lib.lckv_oracle_max_batch.restype = ctypes.c_int64
         lib.lckv_oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -222,3 +228,24 @@ def project(x, W, n_heads: int, pos=None, rope_base: float = 10000.0):
     if rc < 0:
         raise ValueError("lckv_oracle_project: bad argument")
     return out.reshape(B, n_heads, D)
+
+
+def footprint(warm, B: int, T: int, Hkv: int, D: int, elem_bytes: int, rule: int = PAIR_TOP_OF_CONDENSED) -> int:
+    """Bytes of KV cache for B sequences of T positions: every cache the pairing table names keeps K and V of
+    Hkv heads of D elements per position (Sections 1, 2.1)."""
+    warm = np.ascontiguousarray(np.asarray(warm, dtype=np.uint8))
+    n = _load().lckv_oracle_footprint(warm.shape[0], _p(warm, ctypes.c_uint8), rule, B, T, Hkv, D, elem_bytes)
+    if n < 0:
+        raise ValueError("lckv_oracle_footprint: bad argument")
+    return int(n)
+
+
+def max_batch(warm, T: int, Hkv: int, D: int, elem_bytes: int, budget: int, limit: int = 65535,
+              rule: int = PAIR_TOP_OF_CONDENSED) -> int:
+    """Largest batch (at most `limit`) whose caches fit in `budget` bytes (Section 3.1)."""
+    warm = np.ascontiguousarray(np.asarray(warm, dtype=np.uint8))
+    n = _load().lckv_oracle_max_batch(warm.shape[0], _p(warm, ctypes.c_uint8), rule, T, Hkv, D, elem_bytes, budget,
+                                      limit)
+    if n < 0:
+        raise ValueError("lckv_oracle_max_batch: bad argument")
+    return int(n)

@@ -1,4 +1,4 @@
-"""ctypes binding of liblckv.so: the same names as include/lckv.h, argument marshalling only.
+"""ctypes binding of liblckv.so: the same names as include/lckv.h and include/lckv_tools.h, argument marshalling only.
 
 Tensors are torch CUDA (ROCm) tensors used as plain device buffers; their ``data_ptr()`` and the current
 torch stream are passed through.  There is no fallback: without the built library every call raises.
@@ -74,7 +74,7 @@ def lib():
         L.lckv_decode_attention.argtypes = [vp, i32, vp, vp, vp, vp, i32, i32, vp, sz, vp]
         L.lckv_prefill_attention.argtypes = [vp, i32, vp, vp, vp, i32, i32, vp]
         L.lckv_set_prefill_tile.argtypes = [vp, i32]
-        L.lckv_project_qkv.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, i32, ctypes.c_float, vp, sz, vp]
+        L.lckv_project_qkv.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, ctypes.c_float, vp, sz, vp]
         L.lckv_project_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
         L.lckv_pack_projection_weight.argtypes = [vp, vp, vp, i32, i32, vp]
         L.lckv_step.argtypes =[vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
@@ -224,12 +224,13 @@ def lckv_project_workspace_bytes(cache: int, B: int, hidden: int) -> int:
 
 
 def lckv_project_qkv(cache: int, layer: int, x, hidden: int, w_q, w_k, w_v, q_out, dev_seq_lens, B: int,
-                     rope_base: float, workspace, stream=None):
-    _check(lib().lckv_project_qkv(cache, layer, _ptr(x), hidden, _ptr(w_q), _ptr(w_k) if w_k is not None else None,
-                                  _ptr(w_v) if w_v is not None else None, _ptr(q_out), _ptr(dev_seq_lens), B,
-                                  float(rope_base), _ptr(workspace),
-                                  0 if workspace is None else workspace.numel() * workspace.element_size(),
-                                  _stream(stream)),
+                     rope_base: float, workspace, stream=None, k_out=None, v_out=None,
+                     workspace_bytes: Optional[int] = None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lckv_project_qkv(cache, layer, _ptr(x), hidden, _ptr(w_q), _ptr(w_k), _ptr(w_v), _ptr(q_out),
+                                  _ptr(k_out), _ptr(v_out), _ptr(dev_seq_lens), B,
+                                  float(rope_base), _ptr(workspace), workspace_bytes, _stream(stream)),
            "lckv_project_qkv")
 
 

@@ -171,6 +171,7 @@ int attention_impl(lckv_cache *c, int layer, const void *q, void *out, const int
     if (need > 0) {
         if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return LCKV_ERR_WORKSPACE;
     }
+    if (c->host_only) return LCKV_ERR_HIP;
     AttnParams p;
     p.slot = slot_view(c, c->kv_slot[layer]);
     p.q = q;
@@ -214,13 +215,29 @@ int attention_impl(lckv_cache *c, int layer, const void *q, void *out, const int
     return LCKV_OK;
 }
 
-int check_call(const lckv_cache *c, int B, int max_len_hint, int extra) {
+// What every call that touches a slot checks first: the batch fits, a paged cache has its table, and under the
+// sink + window policy the kept positions fit the layout (a ring entry maps to page entry / 16 of the
+// sequence's table row: a row shorter than sink + window would be indexed past its end).
+int check_slot_access(const lckv_cache *c, int B) {
     if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
     if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
-    if (max_len_hint < 0) return LCKV_ERR_LENGTH;
-    if (c->cfg.window_tokens == 0 && (int64_t)max_len_hint + extra > c->capacity) return LCKV_ERR_LENGTH;
     if (c->cfg.window_tokens > 0 && kept_capacity(c) > c->capacity) return LCKV_ERR_BLOCK_TABLE;
     return LCKV_OK;
+}
+
+int check_call(const lckv_cache *c, int B, int max_len_hint, int extra) {
+    int rc = check_slot_access(c, B);
+    if (rc != LCKV_OK) return rc;
+    if (max_len_hint < 0) return LCKV_ERR_LENGTH;
+    if (c->cfg.window_tokens == 0 && (int64_t)max_len_hint + extra > c->capacity) return LCKV_ERR_LENGTH;
+    return LCKV_OK;
+}
+
+// The slot whose K/V `layer` produces, or -1.
+int produced_slot(const lckv_cache *c, int layer) {
+    for (int s = 0; s < c->n_slots; ++s)
+        if (c->producer[s] == layer) return s;
+    return -1;
 }
 
 }  // namespace
@@ -283,7 +300,13 @@ int lckv_cache_alloc(const lckv_config *cfg, void *kv_storage, size_t kv_bytes, 
     c->profiling = false;
     c->ev_used = 0;
     c->dev_err = nullptr;
-    if (hipMalloc((void **)&c->dev_err, 256) != hipSuccess || hipMemset(c->dev_err, 0, 256) != hipSuccess) {
+    // A host without a GPU still gets a handle: the pairing table, the planners and every argument check work
+    // on it, and each call that would enqueue work returns LCKV_ERR_HIP after its checks.
+    int n_dev = 0;
+    c->host_only = hipGetDeviceCount(&n_dev) != hipSuccess || n_dev < 1;
+    if (c->host_only) {
+        (void)hipGetLastError();
+    } else if (hipMalloc((void **)&c->dev_err, 256) != hipSuccess || hipMemset(c->dev_err, 0, 256) != hipSuccess) {
         if (c->dev_err) (void)hipFree(c->dev_err);
         c->magic = 0;
         delete c;
@@ -307,6 +330,7 @@ int lckv_cache_set_block_table(lckv_cache *c, const int32_t *dev_table, int32_t 
     if (!c->cfg.page_size) return LCKV_ERR_BLOCK_TABLE;
     if (max_blocks_per_seq < 1 || max_blocks_per_seq > (1 << 24) / kPage) return LCKV_ERR_BLOCK_TABLE;
     if (!aligned(dev_table, 4)) return LCKV_ERR_ALIGN;
+    if (c->cfg.window_tokens > 0 && kept_capacity(c) > max_blocks_per_seq * kPage) return LCKV_ERR_BLOCK_TABLE;
     c->table = dev_table;
     c->max_blocks = max_blocks_per_seq;
     c->capacity = max_blocks_per_seq * kPage;
@@ -338,13 +362,12 @@ int lckv_append_kv(lckv_cache *c, int32_t layer, const void *k_new, const void *
                    int32_t B, void *hip_stream) {
     if (!valid(c) || !k_new || !v_new || !dev_seq_lens) return LCKV_ERR_NULL;
     if (layer < 0 || layer >= c->cfg.L) return LCKV_ERR_LAYER;
-    int slot = -1;
-    for (int s = 0; s < c->n_slots; ++s)
-        if (c->producer[s] == layer) slot = s;
+    const int slot = produced_slot(c, layer);
     if (slot < 0) return LCKV_ERR_NOT_PRODUCER;
-    if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
-    if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
+    int rc = check_slot_access(c, B);
+    if (rc != LCKV_OK) return rc;
     if (!aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(dev_seq_lens, 4)) return LCKV_ERR_ALIGN;
+    if (c->host_only) return LCKV_ERR_HIP;
     hipError_t e = launch_append(slot_view(c, slot), k_new, v_new, dev_seq_lens, B, c->cfg.D, c->cfg.dtype,
                                  c->dev_err, (hipStream_t)hip_stream);
     return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
@@ -372,6 +395,7 @@ int lckv_prefill_attention(lckv_cache *c, int32_t layer, const void *q, void *ou
     if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
     if (S < 1 || S > c->capacity) return LCKV_ERR_LENGTH;
     if (!aligned(q, 16) || !aligned(out, 16) || !aligned(dev_prompt_lens, 4)) return LCKV_ERR_ALIGN;
+    if (c->host_only) return LCKV_ERR_HIP;
     const lckv_config &cfg = c->cfg;
     AttnParams p;
     p.slot = slot_view(c, c->kv_slot[layer]);
@@ -406,9 +430,10 @@ int lckv_set_prefill_tile(lckv_cache *c, int32_t query_blocks_per_wave) {
     return LCKV_OK;
 }
 
-int lckv_step(lckv_cache *c, const void *q_all, const void *k_new_all, const void *v_new_all, void *out_all,
-              int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint, void *workspace, size_t workspace_bytes,
-              void *hip_stream) {
+// The whole step: argument checks, then the layers in index order on one stream.
+static int step_impl(lckv_cache *c, const void *q_all, const void *k_new_all, const void *v_new_all, void *out_all,
+                     int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint, void *workspace, size_t workspace_bytes,
+                     void *hip_stream) {
     if (!valid(c) || !q_all || !k_new_all || !v_new_all || !out_all || !dev_seq_lens) return LCKV_ERR_NULL;
     int rc = check_call(c, B, max_len_hint, 1);  // the new token must fit
     if (rc != LCKV_OK) return rc;
@@ -418,7 +443,10 @@ int lckv_step(lckv_cache *c, const void *q_all, const void *k_new_all, const voi
     size_t need = 0;
     rc = lckv_workspace_bytes(c, B, max_len_hint, &need);
     if (rc != LCKV_OK) return rc;
-    if (need > 0 && (!workspace || !aligned(workspace, 256) || workspace_bytes < need)) return LCKV_ERR_WORKSPACE;
+    if (need > 0 && (!workspace || !aligned(workspace, 256) || workspace_bytes < need)) {
+        return LCKV_ERR_WORKSPACE;
+    }
+    if (c->host_only) return LCKV_ERR_HIP;
 
     const lckv_config &cfg = c->cfg;
     const size_t eb = (size_t)elem_bytes(cfg.dtype);
@@ -447,6 +475,13 @@ int lckv_step(lckv_cache *c, const void *q_all, const void *k_new_all, const voi
         if (!before && (rc = append_slots_of(l)) != LCKV_OK) return rc;
     }
     return launch_bump(dev_seq_lens, B, stream) == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
+}
+
+int lckv_step(lckv_cache *c, const void *q_all, const void *k_new_all, const void *v_new_all, void *out_all,
+              int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint, void *workspace, size_t workspace_bytes,
+              void *hip_stream) {
+    return step_impl(c, q_all, k_new_all, v_new_all, out_all, dev_seq_lens, B, max_len_hint, workspace,
+                     workspace_bytes, hip_stream);
 }
 
 int lckv_workspace_bytes(const lckv_cache *c, int32_t B, int32_t max_len_hint, size_t *bytes) {
@@ -481,6 +516,7 @@ int lckv_pack_projection_weight(const lckv_cache *c, const void *w, void *w_pack
     if (c->cfg.dtype == LCKV_BF16 && hidden % 256 != 0) return LCKV_ERR_CONFIG;
     if (!aligned(w, 16) || !aligned(w_packed, 16)) return LCKV_ERR_ALIGN;
     if (w == w_packed) return LCKV_ERR_CONFIG;
+    if (c->host_only) return LCKV_ERR_HIP;
     hipError_t e = launch_pack_weight(w, w_packed, n_rows, hidden, c->cfg.dtype, (hipStream_t)hip_stream);
     return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
 }
@@ -494,30 +530,36 @@ int lckv_project_workspace_bytes(const lckv_cache *c, int32_t B, int32_t hidden,
 }
 
 int lckv_project_qkv(lckv_cache *c, int32_t layer, const void *x, int32_t hidden, const void *w_q, const void *w_k,
-                     const void *w_v, void *q_out, const int32_t *dev_seq_lens, int32_t B, float rope_base,
-                     void *workspace, size_t workspace_bytes, void *hip_stream) {
+                     const void *w_v, void *q_out, void *k_out, void *v_out, const int32_t *dev_seq_lens, int32_t B,
+                     float rope_base, void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (!valid(c) || !x || !w_q || !q_out || !dev_seq_lens) return LCKV_ERR_NULL;
     if (layer < 0 || layer >= c->cfg.L) return LCKV_ERR_LAYER;
-    int slot = -1;
-    for (int s = 0; s < c->n_slots; ++s)
-        if (c->producer[s] == layer) slot = s;
-    if (slot < 0 && (w_k || w_v)) return LCKV_ERR_NOT_PRODUCER;
+    const int slot = produced_slot(c, layer);
+    if (slot < 0 && (w_k || w_v || k_out || v_out)) return LCKV_ERR_NOT_PRODUCER;
     if (slot >= 0 && (!w_k || !w_v)) return LCKV_ERR_NULL;
+    if ((k_out == nullptr) != (v_out == nullptr)) return LCKV_ERR_NULL;
+    const bool deferred = k_out != nullptr;
     if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
     if (hidden < 1 || (int64_t)hidden * B > ((int64_t)1 << 40)) return LCKV_ERR_CONFIG;
     if (c->cfg.dtype == LCKV_BF16 && hidden % 256 != 0) return LCKV_ERR_CONFIG;
-    if (slot >= 0 && c->cfg.window_tokens > 0 && !c->self_visible[layer]) return LCKV_ERR_CONFIG;
-    if (slot >= 0 && c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
+    // Under the sink + window policy the shared slot's new K/V replace an entry the producing layer's own
+    // attention still reads: they cannot be stored by this call, only handed back.
+    if (slot >= 0 && !deferred && c->cfg.window_tokens > 0 && !c->self_visible[layer]) return LCKV_ERR_CONFIG;
+    if (slot >= 0 && !deferred) {
+        int rc = check_slot_access(c, B);
+        if (rc != LCKV_OK) return rc;
+    }
     if (!aligned(x, 16) || !aligned(w_q, 16) || !aligned(q_out, 16) || !aligned(dev_seq_lens, 4) ||
-        (w_k && !aligned(w_k, 16)) || (w_v && !aligned(w_v, 16)))
+        (w_k && !aligned(w_k, 16)) || (w_v && !aligned(w_v, 16)) || (deferred && (!aligned(k_out, 16) || !aligned(v_out, 16))))
         return LCKV_ERR_ALIGN;
     size_t need = 0;
     lckv_project_workspace_bytes(c, B, hidden, &need);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return LCKV_ERR_WORKSPACE;
+    if (c->host_only) return LCKV_ERR_HIP;
     float *acc = (float *)workspace;
-    hipError_t e = launch_project(x, hidden, w_q, w_k, w_v, q_out, slot_view(c, slot >= 0 ? slot : 0), dev_seq_lens, B,
-                                  c->cfg.Hq, c->cfg.Hkv, c->cfg.D, c->cfg.dtype, rope_base, acc, c->dev_err,
-                                  (hipStream_t)hip_stream);
+    hipError_t e = launch_project(x, hidden, w_q, w_k, w_v, q_out, k_out, v_out, slot_view(c, slot >= 0 ? slot : 0),
+                                  dev_seq_lens, B, c->cfg.Hq, c->cfg.Hkv, c->cfg.D, c->cfg.dtype, rope_base, acc,
+                                  c->dev_err, (hipStream_t)hip_stream);
     return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
 }
 
@@ -540,9 +582,11 @@ int lckv_cache_load_dense(lckv_cache *c, int32_t slot, const void *k, const void
                           int32_t B, int32_t T, void *hip_stream) {
     if (!valid(c) || !k || !v) return LCKV_ERR_NULL;
     if (slot < 0 || slot >= c->n_slots) return LCKV_ERR_LAYER;
-    if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
-    if (c->cfg.page_size && !c->table) return LCKV_ERR_BLOCK_TABLE;
-    if (T < 0 || T > kept_capacity(c) || kept_capacity(c) > c->capacity) return LCKV_ERR_LENGTH;
+    int rc = check_slot_access(c, B);
+    if (rc != LCKV_OK) return rc;
+    if (T < 0 || T > kept_capacity(c)) return LCKV_ERR_LENGTH;
+    if (!aligned(k, 16) || !aligned(v, 16) || (dev_seq_lens && !aligned(dev_seq_lens, 4))) return LCKV_ERR_ALIGN;
+    if (c->host_only) return LCKV_ERR_HIP;
     hipError_t e = launch_load_dense(slot_view(c, slot), k, v, dev_seq_lens, B, T, c->cfg.D, c->cfg.dtype,
                                      c->dev_err, (hipStream_t)hip_stream);
     return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
@@ -558,6 +602,7 @@ int lckv_cache_read(lckv_cache *c, int32_t slot, int32_t b, int32_t pos, int32_t
     if (pos < 0 || n_pos < 1 || n_pos > kept_capacity(c) || kept_capacity(c) > c->capacity) return LCKV_ERR_RANGE;
     if (c->cfg.window_tokens == 0 && (int64_t)pos + n_pos > c->capacity) return LCKV_ERR_RANGE;
     if ((int64_t)n_pos * c->cfg.Hkv * c->cfg.D >= ((int64_t)1 << 31)) return LCKV_ERR_RANGE;
+    if (c->host_only) return LCKV_ERR_HIP;
     size_t bytes = (size_t)n_pos * c->cfg.Hkv * c->cfg.D * elem_bytes(c->cfg.dtype);
     char *tmp = nullptr;
     if (hipMalloc((void **)&tmp, 2 * bytes) != hipSuccess) return LCKV_ERR_HIP;
@@ -573,6 +618,7 @@ int lckv_cache_read(lckv_cache *c, int32_t slot, int32_t b, int32_t pos, int32_t
 
 int lckv_last_device_error(lckv_cache *c, int32_t *bits) {
     if (!valid(c) || !bits) return LCKV_ERR_NULL;
+    if (c->host_only) return LCKV_ERR_HIP;
     if (hipDeviceSynchronize() != hipSuccess) return LCKV_ERR_HIP;
     if (hipMemcpy(bits, c->dev_err, sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess) return LCKV_ERR_HIP;
     if (*bits && hipMemset(c->dev_err, 0, sizeof(int32_t)) != hipSuccess) return LCKV_ERR_HIP;
@@ -581,6 +627,7 @@ int lckv_last_device_error(lckv_cache *c, int32_t *bits) {
 
 int lckv_profile_enable(lckv_cache *c, int32_t enable) {
     if (!valid(c)) return LCKV_ERR_NULL;
+    if (c->host_only) return LCKV_ERR_HIP;
     if (enable && c->ev.empty()) {
         c->ev.reserve(2 * kProfilePairs);
         for (size_t i = 0; i < 2 * kProfilePairs; ++i) {
@@ -596,6 +643,7 @@ int lckv_profile_enable(lckv_cache *c, int32_t enable) {
 int lckv_profile_launch_ms(lckv_cache *c, float *ms, int32_t capacity, int32_t *n_launches) {
     if (!valid(c) || !ms || !n_launches) return LCKV_ERR_NULL;
     if (capacity < 0) return LCKV_ERR_RANGE;
+    if (c->host_only) return LCKV_ERR_HIP;
     if (hipDeviceSynchronize() != hipSuccess) return LCKV_ERR_HIP;
     int32_t n = 0;
     for (size_t i = 0; i + 1 < c->ev_used && n < capacity; i += 2, ++n)
@@ -606,6 +654,7 @@ int lckv_profile_launch_ms(lckv_cache *c, float *ms, int32_t capacity, int32_t *
 
 int lckv_profile_read(lckv_cache *c, int32_t *n_launches, double *total_ms) {
     if (!valid(c) || !n_launches || !total_ms) return LCKV_ERR_NULL;
+    if (c->host_only) return LCKV_ERR_HIP;
     if (hipDeviceSynchronize() != hipSuccess) return LCKV_ERR_HIP;
     double sum = 0.0;
     for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
@@ -622,6 +671,7 @@ int lckv_profile_read(lckv_cache *c, int32_t *n_launches, double *total_ms) {
 int lckv_hbm_read_probe(lckv_cache *c, const void *dev_buf, size_t bytes, int32_t nontemporal, void *hip_stream) {
     if (!valid(c) || !dev_buf) return LCKV_ERR_NULL;
     if (!aligned(dev_buf, 16)) return LCKV_ERR_ALIGN;
+    if (c->host_only) return LCKV_ERR_HIP;
     hipError_t e = launch_stream_probe(dev_buf, bytes, nontemporal, c->dev_err + 1, (hipStream_t)hip_stream);
     return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
 }

@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "../../include/lckv.h"
+#include "../../include/lckv_tools.h"
 
 namespace lckv {
 
@@ -97,7 +98,7 @@ hipError_t launch_load_dense(const SlotView &v, const void *k, const void *vv, c
 int project_slice_channels(int n_total, int hidden);
 hipError_t launch_pack_weight(const void *src, void *dst, int N, int hidden, int dtype, hipStream_t s);
 hipError_t launch_project(const void *x, int hidden, const void *w_q, const void *w_k, const void *w_v, void *q_out,
-                          const SlotView &slot, const int32_t *seq_lens, int B, int Hq, int Hkv, int D, int dtype,
+                          void *k_out, void *v_out, const SlotView &slot, const int32_t *seq_lens, int B, int Hq, int Hkv, int D, int dtype,
                           float rope_base, float *acc, int32_t *dev_err, hipStream_t s);
 hipError_t launch_stream_probe(const void *buf, size_t bytes, int nontemporal, int32_t *sink, hipStream_t s);
 hipError_t launch_gather(const SlotView &v, int b, int pos, int n_pos, int D, int dtype, void *dev_k, void *dev_v,
@@ -122,6 +123,7 @@ struct lckv_cache {
     int32_t load_policy;          // LCKV_LOAD_*
     int32_t prefill_query_blocks; // 16-position blocks per wave in the bf16 prefill kernel (2 or 4)
     int32_t *dev_err;
+    bool host_only;               // made on a host without a GPU: argument checks and planners only
     float scale;
     // kernel timing
     bool profiling;

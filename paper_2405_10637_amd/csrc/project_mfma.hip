@@ -41,6 +41,7 @@ struct ProjParams {
     int32_t n_slices;
     const int32_t *seq_lens;
     void *q_out;                // [B][Hq][D]
+    void *k_out, *v_out;        // [B][Hkv][D]: if given, the new K/V go there instead of into the slot
     SlotView slot;              // where K/V go (producing layers)
     int32_t Hq, Hkv, D;
     double log2_base;           // log2(rope base); rotate = 0: no rotation
@@ -266,8 +267,14 @@ __device__ __forceinline__ void finish_pair(const ProjParams &p, float2 cs, int 
         q[i + half] = to_elem(hi, E{});
         return;
     }
-    // a key or value head: into the slot at position t_b (the ring entry under the sink + window policy)
     const int g = is_v ? hg - p.Hq - p.Hkv : hg - p.Hq;
+    if (p.k_out) {  // handed back to the caller, who appends them after the layer's attention
+        E *o = (E *)(is_v ? p.v_out : p.k_out) + ((int64_t)b * p.Hkv + g) * p.D;
+        o[i] = to_elem(lo, E{});
+        o[i + half] = to_elem(hi, E{});
+        return;
+    }
+    // a key or value head: into the slot at position t_b (the ring entry under the sink + window policy)
     int t = p.seq_lens[b];
     if (t >= 0) t = entry_of_position(p.slot, t);
     if (t < 0 || t >= p.slot.capacity) {
@@ -311,7 +318,7 @@ int project_slice_channels(int n_total, int hidden) {
 
 // x [B][hidden]; w_k / w_v null for a layer that produces no slot (then `slot` is not used).
 hipError_t launch_project(const void *x, int hidden, const void *w_q, const void *w_k, const void *w_v, void *q_out,
-                          const SlotView &slot, const int32_t *seq_lens, int B, int Hq, int Hkv, int D, int dtype,
+                          void *k_out, void *v_out, const SlotView &slot, const int32_t *seq_lens, int B, int Hq, int Hkv, int D, int dtype,
                           float rope_base, float *acc, int32_t *dev_err, hipStream_t s) {
     ProjParams p{};
     p.x = x;
@@ -327,6 +334,8 @@ hipError_t launch_project(const void *x, int hidden, const void *w_q, const void
     p.acc = acc;
     p.seq_lens = seq_lens;
     p.q_out = q_out;
+    p.k_out = k_out;
+    p.v_out = v_out;
     p.slot = slot;
     p.Hq = Hq;
     p.Hkv = Hkv;

@@ -16,9 +16,12 @@ pytestmark = pytest.mark.skipif(not os.path.exists(lk.LIB_PATH), reason="liblckv
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "lckv.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(lckv_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in ("lckv.h", "lckv_tools.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(lckv_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported_and_bound():
@@ -96,3 +99,98 @@ def test_strerror_names_every_code():
         assert s and "unknown" not in s
         seen.add(s)
     assert len(seen) == 14 and "unknown" in lk.lckv_strerror(-99)
+
+
+# --- Argument checks of the enqueueing calls, on a handle made without a GPU -----------------------------------
+# (lckv_cache_alloc on a host without a GPU returns a handle on which every check runs and every call that would
+# enqueue work ends in LCKV_ERR_HIP; on a GPU machine the same checks run before the launch.)
+
+FAKE = 0x10000  # an aligned, non-null "device" address that no check dereferences
+
+
+def host_handle(wl, **kw):
+    cfg = cfg_for(wl, **kw)
+    h = ctypes.c_void_p(None)
+    rc = lk.lib().lckv_cache_alloc(ctypes.byref(cfg), FAKE, 1 << 62, ctypes.byref(h))
+    assert rc == lk.LCKV_OK and h.value
+    return h.value, cfg
+
+
+def code_of(fn, *a, **kw):
+    try:
+        fn(*a, **kw)
+    except lk.LckvError as e:
+        return e.code
+    return lk.LCKV_OK
+
+
+def test_pairing_table_of_the_library_equals_the_oracles_on_the_host():
+    from oracle import lckv_oracle as orc
+    for wl in (synth.C1, synth.C2, synth.C5):
+        for rule in (lk.LCKV_PAIR_TOP_OF_CONDENSED, lk.LCKV_PAIR_LAST_LAYER):
+            h, _ = host_handle(wl, pairing_rule=rule)
+            kv_slot, vis, prod = orc.pairing(wl.warmup_mask, rule)
+            assert lk.lckv_n_slots(h) == len(prod)
+            assert [lk.lckv_kv_slot(h, l) for l in range(wl.L)] == list(zip(kv_slot.tolist(), vis.tolist()))
+            assert [lk.lckv_slot_producer(h, s) for s in range(len(prod))] == prod.tolist()
+            lk.lckv_cache_free(h)
+
+
+def test_sink_window_must_fit_the_block_table_in_every_call_that_indexes_it():
+    # Section 3.3 policy on a paged cache: a ring entry maps to page entry/16 of the sequence's table row, so a
+    # row shorter than sink + window would be indexed past its end by the append and the projections' append.
+    wl = synth.Workload("bt", "bf16", L=3, w=1, Hq=4, Hkv=2, D=64, B=2, T=64, seed=1)
+    h, _ = host_handle(wl, page_size=16, num_blocks=64, T_max=0, sink_tokens=4, window_tokens=60)
+    assert code_of(lk.lckv_cache_set_block_table, h, FAKE, 3) == lk.LCKV_ERR_BLOCK_TABLE   # 48 < 64 positions
+    # no table at all: every call that touches a slot refuses
+    assert code_of(lk.lckv_append_kv, h, 0, FAKE, FAKE, FAKE, 2, stream=0) == lk.LCKV_ERR_BLOCK_TABLE
+    assert code_of(lk.lckv_cache_load_dense, h, 0, FAKE, FAKE, None, 2, 16, stream=0) == lk.LCKV_ERR_BLOCK_TABLE
+    assert code_of(lk.lckv_project_qkv, h, 0, FAKE, 256, FAKE, FAKE, FAKE, FAKE, FAKE, 2, 1e4, FAKE,
+                   stream=0, workspace_bytes=1 << 30) == lk.LCKV_ERR_BLOCK_TABLE
+    lk.lckv_cache_set_block_table(h, FAKE, 4)                                              # 64 positions: fits
+    assert code_of(lk.lckv_append_kv, h, 0, FAKE, FAKE, FAKE, 2, stream=0) == lk.LCKV_ERR_HIP   # checks passed
+    lk.lckv_cache_free(h)
+
+
+def test_argument_errors_of_the_step_and_attention_calls():
+    wl = synth.Workload("args", "bf16", L=4, w=2, Hq=8, Hkv=2, D=128, B=4, T=1000, seed=2)
+    h, _ = host_handle(wl)
+    cap = (wl.T + 1 + 15) // 16 * 16
+    step = lambda *a, **k: code_of(lk.lckv_step, h, *a, stream=0, **k)
+    assert step(FAKE, FAKE, FAKE, FAKE, FAKE, 5, 100) == lk.LCKV_ERR_BATCH
+    assert step(FAKE, FAKE, FAKE, FAKE, FAKE, 4, cap) == lk.LCKV_ERR_LENGTH          # the new token must fit
+    assert step(FAKE + 2, FAKE, FAKE, FAKE, FAKE, 4, 100) == lk.LCKV_ERR_ALIGN
+    lk.lckv_set_split_tokens(h, 64)
+    need = lk.lckv_workspace_bytes(h, 4, 1000)
+    assert need == 16 * 4 * 8 * 128 * 4 + 16 * 4 * 8 * 8                              # 16 splits: o partials + (m, l)
+    assert step(FAKE, FAKE, FAKE, FAKE, FAKE, 4, 1000) == lk.LCKV_ERR_WORKSPACE       # splits need a workspace
+    assert step(FAKE, FAKE, FAKE, FAKE, FAKE, 4, 1000, workspace=FAKE, workspace_bytes=need - 1) == lk.LCKV_ERR_WORKSPACE
+    assert step(FAKE, FAKE, FAKE, FAKE, FAKE, 4, 1000, workspace=FAKE, workspace_bytes=need) == lk.LCKV_ERR_HIP
+    att = lambda layer, mask, **k: code_of(lk.lckv_decode_attention, h, layer, FAKE, FAKE, FAKE, mask, 4, 100,
+                                           stream=0, **k)
+    assert att(4, None) == lk.LCKV_ERR_LAYER
+    assert att(0, [1, 1, 0, 0]) == lk.LCKV_ERR_MASK
+    assert att(0, wl.warmup_mask, workspace=FAKE, workspace_bytes=1 << 30) == lk.LCKV_ERR_HIP
+    assert code_of(lk.lckv_append_kv, h, 1, FAKE, FAKE, FAKE, 4, stream=0) == lk.LCKV_ERR_NOT_PRODUCER
+    lk.lckv_cache_free(h)
+
+
+def test_projection_argument_rules():
+    # Section 2.1: only producing layers have W_K, W_V; Section 3.3: under the sink + window policy the condensed
+    # producer's new K/V can only be handed back, not stored at once
+    wl = synth.Workload("proj", "bf16", L=4, w=2, Hq=4, Hkv=2, D=64, B=2, T=32, seed=4)
+    h, _ = host_handle(wl, sink_tokens=4, window_tokens=28)
+    producer_condensed = 2                                      # warmup {0, 3}; topmost condensed layer is 2
+    assert [lk.lckv_slot_producer(h, s) for s in range(3)] == [0, 2, 3]
+    pr = lambda layer, wk, wv, ko=None, vo=None, ws=1 << 30: code_of(
+        lk.lckv_project_qkv, h, layer, FAKE, 256, FAKE, wk, wv, FAKE, FAKE, 2, 1e4, FAKE if ws else None,
+        stream=0, k_out=ko, v_out=vo, workspace_bytes=ws)
+    assert pr(1, FAKE, FAKE) == lk.LCKV_ERR_NOT_PRODUCER
+    assert pr(1, None, None, FAKE, FAKE) == lk.LCKV_ERR_NOT_PRODUCER
+    assert pr(0, FAKE, None) == lk.LCKV_ERR_NULL
+    assert pr(0, FAKE, FAKE, FAKE, None) == lk.LCKV_ERR_NULL
+    assert pr(producer_condensed, FAKE, FAKE) == lk.LCKV_ERR_CONFIG
+    assert pr(producer_condensed, FAKE, FAKE, FAKE, FAKE) == lk.LCKV_ERR_HIP      # deferred: accepted
+    assert pr(0, FAKE, FAKE) == lk.LCKV_ERR_HIP                                   # warmup layer stores at once
+    assert pr(1, None, None) == lk.LCKV_ERR_HIP
+    lk.lckv_cache_free(h)

@@ -193,21 +193,27 @@ def test_condensed_layers_with_equal_queries_give_bitwise_equal_outputs_and_batc
     assert torch.equal(outs[0][:, perm], outs[1])                                        # bitwise
 
 
-def test_load_policy_does_not_change_a_bit():
-    # plain and nontemporal loads read the same bytes: outputs must be bitwise equal, contiguous and paged
-    for paged in (False, True):
-        wl = synth.Workload("t-policy", "bf16", L=3, w=1, Hq=8, Hkv=4, D=128, B=3, T=260, sigma=1.0, seed=25,
-                            paged=paged)
-        lens = np.array([260, 33, 128], np.int32)
-        K, V = synth.logical_cache(wl, 2, 260)
-        q, kn, vn = synth.step_inputs(wl, 2)
-        outs = []
-        for policy in (lk.LCKV_LOAD_TEMPORAL, lk.LCKV_LOAD_NONTEMPORAL):
-            with GpuCache(wl, 272, lens, split_tokens=64, load_policy=policy) as gc:
-                for s in range(2):
-                    gc.load_dense(s, K[s], V[s])
-                outs.append(gc.step(q, kn, vn).cpu())
-        assert torch.equal(outs[0], outs[1]) and torch.isfinite(outs[0].float()).all()
+@pytest.mark.parametrize("D,Hq,Hkv", [(128, 8, 4), (64, 16, 2), (64, 4, 4)])
+@pytest.mark.parametrize("paged", [False, True])
+def test_load_policy_does_not_change_a_bit(D, Hq, Hkv, paged):
+    # plain and nontemporal loads read the same bytes: outputs must be bitwise equal (contiguous and paged, both
+    # head dimensions, grouped and ungrouped heads), and the forced-nontemporal result must match the oracle
+    wl = synth.Workload("t-policy", "bf16", L=3, w=1, Hq=Hq, Hkv=Hkv, D=D, B=3, T=260, sigma=1.0, seed=25,
+                        paged=paged)
+    lens = np.array([260, 33, 128], np.int32)
+    K, V = synth.logical_cache(wl, 2, 272)
+    q, kn, vn = synth.step_inputs(wl, 2)
+    outs = []
+    for policy in (lk.LCKV_LOAD_TEMPORAL, lk.LCKV_LOAD_NONTEMPORAL):
+        with GpuCache(wl, 272, lens, split_tokens=64, load_policy=policy) as gc:
+            for s in range(2):
+                gc.load_dense(s, K[s, :, :260], V[s, :, :260])
+            outs.append(gc.step(q, kn, vn).cpu())
+            assert gc.device_error() == 0
+    assert torch.equal(outs[0], outs[1]) and torch.isfinite(outs[0].float()).all()
+    want, _ = orc.step(wl.warmup_mask, to_f32_numpy(K), to_f32_numpy(V), lens.copy(), to_f32_numpy(q),
+                       to_f32_numpy(kn), to_f32_numpy(vn), 1.0 / np.sqrt(D))
+    check_close(outs[1], want, "bf16", "nontemporal loads, D=%d paged=%s" % (D, paged))
 
 
 def test_new_shared_kv_is_invisible_now_and_visible_next_step():

@@ -124,8 +124,8 @@ def test_project_argument_errors():
         ws = torch.empty(lk.lckv_project_workspace_bytes(gc.h, 2, 256), dtype=torch.uint8, device="cuda")
         p, w, n = t.data_ptr(), ws.data_ptr(), ws.numel()
         st = torch.cuda.current_stream().cuda_stream or None
-        call = lambda layer, hidden=256, wk=p, wv=p, B=2, wsp=w, wsn=n: L.lckv_project_qkv(
-            gc.h, layer, p, hidden, p, wk, wv, p, gc.lens.data_ptr(), B, 10000.0, wsp, wsn, st)
+        call = lambda layer, hidden=256, wk=p, wv=p, B=2, wsp=w, wsn=n, ko=None, vo=None: L.lckv_project_qkv(
+            gc.h, layer, p, hidden, p, wk, wv, p, ko, vo, gc.lens.data_ptr(), B, 10000.0, wsp, wsn, st)
         producers = [lk.lckv_slot_producer(gc.h, s) for s in range(gc.n_slots)]
         other = [l for l in range(wl.L) if l not in producers][0]
         # workspace = fp32 partial sums [hidden slices][B][(Hq + 2 Hkv) D]: one slice of 256 channels here,
@@ -136,6 +136,8 @@ def test_project_argument_errors():
             lk.lckv_project_workspace_bytes(gc.h, 2, 100)
         assert call(other) == lk.LCKV_ERR_NOT_PRODUCER            # such a layer has no W_K, W_V
         assert call(other, wk=None, wv=None) == lk.LCKV_OK
+        assert call(other, wk=None, wv=None, ko=p, vo=p) == lk.LCKV_ERR_NOT_PRODUCER
+        assert call(producers[0], ko=p) == lk.LCKV_ERR_NULL       # both of k_out, v_out or neither
         assert call(producers[0], wk=None) == lk.LCKV_ERR_NULL and call(producers[0], wv=None) == lk.LCKV_ERR_NULL
         assert call(producers[0], hidden=128) == lk.LCKV_ERR_CONFIG
         assert call(7) == lk.LCKV_ERR_LAYER and call(producers[0], B=3) == lk.LCKV_ERR_BATCH
@@ -147,8 +149,11 @@ def test_project_argument_errors():
         torch.cuda.synchronize()
     with GpuCache(wl, 32, np.array([3, 4], np.int32), sink=4, window=28) as gc:
         shared = [l for l in producers if not lk.lckv_kv_slot(gc.h, l)[1]][0]
-        assert L.lckv_project_qkv(gc.h, shared, p, 256, p, p, p, p, gc.lens.data_ptr(), 2, 10000.0, w, n, st) == \
-            lk.LCKV_ERR_CONFIG
+        assert L.lckv_project_qkv(gc.h, shared, p, 256, p, p, p, p, None, None, gc.lens.data_ptr(), 2, 10000.0, w, n,
+                                  st) == lk.LCKV_ERR_CONFIG     # storing at once would overwrite a visible entry
+        assert L.lckv_project_qkv(gc.h, shared, p, 256, p, p, p, p, p, p + 4096, gc.lens.data_ptr(), 2, 10000.0, w, n,
+                                  st) == lk.LCKV_OK             # handed back instead: accepted
+        torch.cuda.synchronize()
 
 
 def test_decode_steps_from_hidden_states():
@@ -258,3 +263,71 @@ def test_projection_attention_and_prompt_encoding_replay_from_a_hip_graph():
             graphed.lens += 1                                            # eager work between the replays
             eager.lens += 1
         assert graphed.device_error() == 0 and eager.device_error() == 0
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_streaming_decode_steps_from_hidden_states(paged):
+    # Sections 2.1 and 3.3 together: under the sink + window policy every layer is driven from its hidden state.
+    # Warmup layers project and store at once (they see the new token); the condensed layer that owns the shared
+    # slot gets its rotated K/V handed back (k_out, v_out) and they are appended after its attention, when no
+    # condensed layer of the step reads the ring entry they replace any more.  The ring wraps several times.  The
+    # oracle keeps the whole history and projects with its own routine.
+    wl = synth.Workload("pr-stream", "bf16", L=4, w=2, Hq=4, Hkv=2, D=64, B=3, T=24, sigma=1.0, seed=71, paged=paged)
+    hidden, sink, window, steps = 256, 4, 20, 55
+    lens = np.array([24, 0, 9], np.int32)
+    T_hist = int(lens.max()) + steps + 1
+    scale = 1.0 / np.sqrt(wl.D)
+    print("streaming from hidden states: sink", sink, "window", window, "steps", steps, "paged", paged, flush=True)
+    with GpuCache(wl, 32 if paged else sink + window, lens, sink=sink, window=window) as gc:
+        ns = gc.n_slots
+        K0, V0 = synth.logical_cache(wl, ns, T_hist)
+        for s in range(ns):
+            gc.load_dense(s, K0[s, :, :24], V0[s, :, :24])
+        Kf, Vf = to_f32_numpy(K0), to_f32_numpy(V0)                      # the oracle's full history
+        producers = {lk.lckv_slot_producer(gc.h, s): s for s in range(ns)}
+        W = [weights(wl, hidden, l, l in producers) for l in range(wl.L)]
+        Wd = [[packed(gc.h, t) for t in w] for w in W]
+        ws = torch.empty(lk.lckv_project_workspace_bytes(gc.h, wl.B, hidden), dtype=torch.uint8, device="cuda")
+        kbuf = torch.full((wl.B, wl.Hkv, wl.D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        vbuf = torch.full_like(kbuf, float("nan"))
+        lens_o = lens.copy()
+        rb = lambda a: to_f32_numpy(torch.from_numpy(a).to(torch.bfloat16))
+        for step in range(steps):
+            hint = int(lens_o.max())
+            aws = gc.workspace(hint)
+            for l in range(wl.L):
+                x = synth._normal((wl.B, hidden), 1.0, torch.bfloat16, 9000 + 10 * step + l)
+                q = torch.empty((wl.B, wl.Hq, wl.D), dtype=torch.bfloat16, device="cuda")
+                out = torch.full_like(q, float("nan"))
+                slot, vis = lk.lckv_kv_slot(gc.h, l)
+                deferred = l in producers and not vis
+                lk.lckv_project_qkv(gc.h, l, x.cuda(), hidden, Wd[l][0], Wd[l][1], Wd[l][2], q, gc.lens, wl.B,
+                                    10000.0, ws, k_out=kbuf if deferred else None, v_out=vbuf if deferred else None)
+                lk.lckv_decode_attention(gc.h, l, q, out, gc.lens, None, wl.B, hint, workspace=aws)
+                if deferred:
+                    lk.lckv_append_kv(gc.h, l, kbuf, vbuf, gc.lens, wl.B)
+                torch.cuda.synchronize()
+                xf = to_f32_numpy(x)
+                qo = rb(orc.project(xf, to_f32_numpy(W[l][0]), wl.Hq, pos=lens_o))
+                if l in producers:
+                    ko = rb(orc.project(xf, to_f32_numpy(W[l][1]), wl.Hkv, pos=lens_o))
+                    vo = rb(orc.project(xf, to_f32_numpy(W[l][2]), wl.Hkv))
+                    if deferred:                                     # what was handed back is what the oracle projects
+                        assert np.abs(kbuf.float().cpu().numpy() - ko).max() <= 4e-2
+                        assert np.abs(vbuf.float().cpu().numpy() - vo).max() <= 4e-2
+                    for b in range(wl.B):
+                        Kf[producers[l], b, lens_o[b]], Vf[producers[l], b, lens_o[b]] = ko[b], vo[b]
+                want = np.zeros((wl.B, wl.Hq, wl.D))
+                for b in range(wl.B):
+                    n = int(lens_o[b]) + (1 if vis else 0)           # candidates; kept: sinks + the last `window`
+                    kept = list(range(min(sink, n))) + list(range(max(sink, n - window), n))
+                    for h in range(wl.Hq):
+                        g = h // (wl.Hq // wl.Hkv)
+                        if kept:
+                            want[b, h] = orc.attend(qo[b, h], Kf[slot, b, kept, g], Vf[slot, b, kept, g], scale)
+                g_ = out.float().cpu().numpy()
+                assert np.isfinite(g_).all()
+                assert np.abs(g_ - want).max() <= 4e-2, "step %d layer %d: %g" % (step, l, np.abs(g_ - want).max())
+            gc.lens += 1
+            lens_o += 1
+        assert gc.device_error() == 0

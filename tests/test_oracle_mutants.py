@@ -9,6 +9,7 @@ from oracle import lckv_oracle as orc
 import test_oracle_pins as pins
 import test_oracle_prefill_pins as prefill_pins
 import test_oracle_project_pins as project_pins
+import test_oracle_footprint_pins as footprint_pins
 
 SRC = os.path.join(os.path.dirname(orc.__file__), "lckv_oracle.c")
 
@@ -51,10 +52,17 @@ MUTANTS = {
                                        "const double lo = v[2 * i], hi = v[2 * i + 1];\n"
                                        "                v[2 * i] = lo * c - hi * s;\n"
                                        "                v[2 * i + 1] = hi * c + lo * s;"),
+    "footprint: values not counted": ("                   + T * (int64_t)Hkv * D * elem_bytes;  /* and its values    */",
+                                      "                   ;"),
+    "footprint: every layer keeps a cache": ("for (int s = 0; s < n_slots; ++s)          /* every cache that is kept    */",
+                                             "for (int s = 0; s < L; ++s)"),
+    "footprint: query heads counted": ("bytes += T * (int64_t)Hkv * D * elem_bytes   /* its keys          */",
+                                       "bytes += T * (int64_t)Hkv * 8 * D * elem_bytes"),
+    "planner: one sequence too many": ("B + 1, T, Hkv, D, elem_bytes) <= budget)", "B, T, Hkv, D, elem_bytes) <= budget)"),
     "rope: only the first head rotated": ("double *v = y + (int64_t)h * D;", "double *v = y + (int64_t)(h > 0 ? 0 : h) * D;"),
 }
 
-PIN_FUNCS = [getattr(mod, n) for mod in (pins, prefill_pins, project_pins) for n in dir(mod) if n.startswith("test_")]
+PIN_FUNCS = [getattr(mod, n) for mod in (pins, prefill_pins, project_pins, footprint_pins) for n in dir(mod) if n.startswith("test_")]
 
 
 def _run_all_pins():
