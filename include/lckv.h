@@ -69,6 +69,10 @@ extern "C" {
 #define LCKV_DEV_ERR_CAPACITY 1     /* a sequence length reached the capacity; the access was skipped/clamped */
 #define LCKV_DEV_ERR_BLOCK 2        /* a block-table entry was outside [0, num_blocks); the page was skipped */
 
+/* Size of the library's own scratch array (device memory inside the loaded library, one copy per GPU), used by
+ * lckv_step_static_scratch. */
+#define LCKV_STATIC_SCRATCH_BYTES (32u << 20)
+
 typedef struct lckv_cache lckv_cache; /* opaque */
 
 typedef struct lckv_config {
@@ -209,6 +213,18 @@ int lckv_pack_projection_weight(const lckv_cache *cache, const void *w, void *w_
 int lckv_step(lckv_cache *cache, const void *q_all, const void *k_new_all, const void *v_new_all, void *out_all,
               int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint, void *workspace, size_t workspace_bytes,
               void *hip_stream);
+
+/* lckv_step for callers that cannot allocate device memory and so have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace,
+ * same kernels, same results bit for bit; the split partials go to the library's own scratch array of
+ * LCKV_STATIC_SCRATCH_BYTES (part of the loaded library, one copy per GPU, held until the process ends).  The
+ * call allocates nothing.  LCKV_ERR_WORKSPACE if lckv_workspace_bytes for this B and max_len_hint exceeds
+ * LCKV_STATIC_SCRATCH_BYTES.  Nothing in the array has to start at zero (every split writes its partial before
+ * the merge reads it), and it keeps the last call's contents.  All handles and all calls on one GPU share that
+ * GPU's array: calls that overlap in time on one GPU (two streams, two threads) race - serialise them. */
+int lckv_step_static_scratch(lckv_cache *cache, const void *q_all, const void *k_new_all, const void *v_new_all,
+                             void *out_all, int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint,
+                             void *hip_stream);
 
 /* Bytes of workspace lckv_decode_attention / lckv_step need for this B and max_len_hint.  Host only. */
 int lckv_workspace_bytes(const lckv_cache *cache, int32_t B, int32_t max_len_hint, size_t *bytes);

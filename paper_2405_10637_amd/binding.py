@@ -22,11 +22,13 @@ LCKV_BF16, LCKV_F32 = 0, 1
 LCKV_PAIR_TOP_OF_CONDENSED, LCKV_PAIR_LAST_LAYER = 0, 1
 LCKV_DEV_ERR_CAPACITY, LCKV_DEV_ERR_BLOCK = 1, 2
 LCKV_LOAD_AUTO, LCKV_LOAD_TEMPORAL, LCKV_LOAD_NONTEMPORAL = 0, 1, 2
+LCKV_STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = [
     "lckv_cache_bytes", "lckv_plan_max_batch", "lckv_cache_alloc", "lckv_cache_free", "lckv_cache_set_block_table", "lckv_n_slots",
     "lckv_kv_slot", "lckv_slot_producer", "lckv_append_kv", "lckv_decode_attention", "lckv_prefill_attention",
     "lckv_set_prefill_tile", "lckv_project_qkv", "lckv_project_workspace_bytes", "lckv_pack_projection_weight", "lckv_step",
+    "lckv_step_static_scratch",
     "lckv_workspace_bytes", "lckv_set_split_tokens", "lckv_set_load_policy", "lckv_cache_load_dense", "lckv_cache_read",
     "lckv_last_device_error", "lckv_profile_enable", "lckv_profile_read", "lckv_profile_launch_ms",
     "lckv_hbm_read_probe", "lckv_strerror",
@@ -78,6 +80,7 @@ def lib():
         L.lckv_project_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
         L.lckv_pack_projection_weight.argtypes = [vp, vp, vp, i32, i32, vp]
         L.lckv_step.argtypes =[vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
+        L.lckv_step_static_scratch.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp]
         L.lckv_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
         L.lckv_set_split_tokens.argtypes = [vp, i32]
         L.lckv_set_load_policy.argtypes = [vp, i32]
@@ -210,6 +213,13 @@ def lckv_step(cache: int, q_all, k_new_all, v_new_all, out_all, dev_seq_lens, B:
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lckv_step(cache, _ptr(q_all), _ptr(k_new_all), _ptr(v_new_all), _ptr(out_all), _ptr(dev_seq_lens), B,
                            max_len_hint, _ptr(workspace), workspace_bytes, _stream(stream)), "lckv_step")
+
+
+def lckv_step_static_scratch(cache: int, q_all, k_new_all, v_new_all, out_all, dev_seq_lens, B: int, max_len_hint: int,
+                             stream=None):
+    _check(lib().lckv_step_static_scratch(cache, _ptr(q_all), _ptr(k_new_all), _ptr(v_new_all), _ptr(out_all),
+                                          _ptr(dev_seq_lens), B, max_len_hint, _stream(stream)),
+           "lckv_step_static_scratch")
 
 
 def lckv_pack_projection_weight(cache: int, w, w_packed, n_rows: int, hidden: int, stream=None):

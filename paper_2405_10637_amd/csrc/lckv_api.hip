@@ -2,13 +2,37 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "lckv_internal.h"
 
 using namespace lckv;
 
+// Scratch of lckv_step_static_scratch, the entry point for callers that cannot allocate: device memory that is
+// part of the loaded library, one copy per GPU, held until the process ends.  The name is a host-side stand-in,
+// never a device address: host code uses the pointer hipGetSymbolAddress returns for the current device.
+static __device__ __align__(256) unsigned char scratch[LCKV_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];  // per device: where that GPU's copy of `scratch` lives
+
+// The current device's copy of `scratch`; asked of the runtime once per device, with that device current.
+int static_scratch_of_current_device(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LCKV_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return LCKV_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return LCKV_OK;
+}
 
 constexpr uint64_t kMagic = 0x4c434b5643414348ull;  // "LCKVCACH"
 constexpr size_t kProfilePairs = 4096;
@@ -300,13 +324,15 @@ int lckv_cache_alloc(const lckv_config *cfg, void *kv_storage, size_t kv_bytes, 
     c->profiling = false;
     c->ev_used = 0;
     c->dev_err = nullptr;
+    c->scratch = nullptr;
     // A host without a GPU still gets a handle: the pairing table, the planners and every argument check work
     // on it, and each call that would enqueue work returns LCKV_ERR_HIP after its checks.
     int n_dev = 0;
     c->host_only = hipGetDeviceCount(&n_dev) != hipSuccess || n_dev < 1;
     if (c->host_only) {
         (void)hipGetLastError();
-    } else if (hipMalloc((void **)&c->dev_err, 256) != hipSuccess || hipMemset(c->dev_err, 0, 256) != hipSuccess) {
+    } else if (hipMalloc((void **)&c->dev_err, 256) != hipSuccess || hipMemset(c->dev_err, 0, 256) != hipSuccess ||
+               static_scratch_of_current_device(&c->scratch) != LCKV_OK) {
         if (c->dev_err) (void)hipFree(c->dev_err);
         c->magic = 0;
         delete c;
@@ -430,10 +456,10 @@ int lckv_set_prefill_tile(lckv_cache *c, int32_t query_blocks_per_wave) {
     return LCKV_OK;
 }
 
-// The whole step: argument checks, then the layers in index order on one stream.
+// Both forms of the whole step: argument checks, then the layers in index order on one stream.
 static int step_impl(lckv_cache *c, const void *q_all, const void *k_new_all, const void *v_new_all, void *out_all,
                      int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint, void *workspace, size_t workspace_bytes,
-                     void *hip_stream) {
+                     bool static_scratch, void *hip_stream) {
     if (!valid(c) || !q_all || !k_new_all || !v_new_all || !out_all || !dev_seq_lens) return LCKV_ERR_NULL;
     int rc = check_call(c, B, max_len_hint, 1);  // the new token must fit
     if (rc != LCKV_OK) return rc;
@@ -443,7 +469,12 @@ static int step_impl(lckv_cache *c, const void *q_all, const void *k_new_all, co
     size_t need = 0;
     rc = lckv_workspace_bytes(c, B, max_len_hint, &need);
     if (rc != LCKV_OK) return rc;
-    if (need > 0 && (!workspace || !aligned(workspace, 256) || workspace_bytes < need)) {
+    if (static_scratch) {
+        if (need > (size_t)LCKV_STATIC_SCRATCH_BYTES) return LCKV_ERR_WORKSPACE;
+        if (c->host_only) return LCKV_ERR_HIP;
+        if ((rc = static_scratch_of_current_device(&workspace)) != LCKV_OK) return rc;
+        workspace_bytes = LCKV_STATIC_SCRATCH_BYTES;
+    } else if (need > 0 && (!workspace || !aligned(workspace, 256) || workspace_bytes < need)) {
         return LCKV_ERR_WORKSPACE;
     }
     if (c->host_only) return LCKV_ERR_HIP;
@@ -481,7 +512,14 @@ int lckv_step(lckv_cache *c, const void *q_all, const void *k_new_all, const voi
               int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint, void *workspace, size_t workspace_bytes,
               void *hip_stream) {
     return step_impl(c, q_all, k_new_all, v_new_all, out_all, dev_seq_lens, B, max_len_hint, workspace,
-                     workspace_bytes, hip_stream);
+                     workspace_bytes, false, hip_stream);
+}
+
+int lckv_step_static_scratch(lckv_cache *c, const void *q_all, const void *k_new_all, const void *v_new_all,
+                             void *out_all, int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint,
+                             void *hip_stream) {
+    return step_impl(c, q_all, k_new_all, v_new_all, out_all, dev_seq_lens, B, max_len_hint, nullptr, 0, true,
+                     hip_stream);
 }
 
 int lckv_workspace_bytes(const lckv_cache *c, int32_t B, int32_t max_len_hint, size_t *bytes) {

@@ -123,6 +123,7 @@ struct lckv_cache {
     int32_t load_policy;          // LCKV_LOAD_*
     int32_t prefill_query_blocks; // 16-position blocks per wave in the bf16 prefill kernel (2 or 4)
     int32_t *dev_err;
+    void *scratch;                // this device's copy of the library's static scratch array
     bool host_only;               // made on a host without a GPU: argument checks and planners only
     float scale;
     // kernel timing

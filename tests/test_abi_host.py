@@ -175,6 +175,21 @@ def test_argument_errors_of_the_step_and_attention_calls():
     lk.lckv_cache_free(h)
 
 
+def test_static_scratch_entry_point_rejects_what_does_not_fit():
+    # the variant of lckv_step for callers that cannot allocate: same checks, and a bound on the split partials
+    wl = synth.Workload("static", "bf16", L=4, w=2, Hq=32, Hkv=32, D=128, B=128, T=4096, seed=3)
+    h, _ = host_handle(wl)
+    stat = lambda B, hint: code_of(lk.lckv_step_static_scratch, h, FAKE, FAKE, FAKE, FAKE, FAKE, B, hint, stream=0)
+    assert lk.lckv_workspace_bytes(h, 128, 4096) == 0
+    assert stat(128, 4096) == lk.LCKV_ERR_HIP                     # fits (no scratch at all): only the GPU is missing
+    assert stat(129, 4096) == lk.LCKV_ERR_BATCH
+    lk.lckv_set_split_tokens(h, 256)                              # 17 splits of 128 x 32 rows x 128 channels: 35 MiB
+    assert lk.lckv_workspace_bytes(h, 128, 4096) > lk.LCKV_STATIC_SCRATCH_BYTES
+    assert stat(128, 4096) == lk.LCKV_ERR_WORKSPACE
+    assert stat(64, 4096) == lk.LCKV_ERR_HIP
+    lk.lckv_cache_free(h)
+
+
 def test_projection_argument_rules():
     # Section 2.1: only producing layers have W_K, W_V; Section 3.3: under the sink + window policy the condensed
     # producer's new K/V can only be handed back, not stored at once
