@@ -135,10 +135,12 @@ def residency_sweep(steps, warmup):
                       "last_level_cache_MiB": 256, "rows": rows}))
 
 
-def prefill_bench(steps, warmup, tile):
+def prefill_bench(steps, warmup, tile, with_import=False, S=2048, B=16):
     """Prompt-encoding attention (lckv_prefill_attention, one condensed layer over the whole prompt), Llama-7B
     shape, bf16: B=16 prompts of S=2048 tokens.  Compute-bound: reported against the bf16 matrix-core peak.
-    Checks a sample of rows against the oracle.  Prints one JSON line."""
+    Checks a sample of rows against the oracle.  With `with_import` a step is what one iteration of the prompt
+    encoding does for this layer (Section 2.3): the import of the producing layer's K/V of all prompt tokens
+    (lckv_cache_load_dense) followed by the attention that reads them.  Prints one JSON line."""
     import numpy as np
     import torch
     from oracle import lckv_oracle as orc
@@ -146,8 +148,7 @@ def prefill_bench(steps, warmup, tile):
     from paper_2405_10637_amd import synth
     from paper_2405_10637_amd.runner import DecodeSession
 
-    S = 2048
-    wl = synth.C3.with_(B=16, T=S, name="prefill-llama-7b-B16-S2048")
+    wl = synth.C3.with_(B=B, T=S, name="prefill-llama-7b-B%d-S%d" % (B, S))
     with DecodeSession(wl, room=16) as sess:
         if tile:
             lk.lckv_set_prefill_tile(sess.h, tile)
@@ -157,11 +158,32 @@ def prefill_bench(steps, warmup, tile):
         kv = sess.fill(units)
         q = synth._normal((wl.B, S, wl.Hq, wl.D), wl.sigma, wl.torch_dtype, wl.seed + 9, device="cuda")
         out = torch.empty_like(q)
-        run = lambda: lk.lckv_prefill_attention(sess.h, layer, q, out, sess.lens, wl.B, S)
+        attend = lambda: lk.lckv_prefill_attention(sess.h, layer, q, out, sess.lens, wl.B, S)
+        # the dense K/V the iteration's producing layer hands over (same seeds as fill(): the cache content stays)
+        Kd = torch.empty((wl.B, S, wl.Hkv, wl.D), dtype=wl.torch_dtype, device="cuda")
+        Vd = torch.empty_like(Kd)
+        synth.fill_normal_(Kd, wl.sigma, wl.seed * 31 + 2 * slot)
+        synth.fill_normal_(Vd, wl.sigma, wl.seed * 31 + 2 * slot + 1)
+        load = lambda: lk.lckv_cache_load_dense(sess.h, slot, Kd, Vd, sess.lens, wl.B, S)
+
+        def timed(fn, n):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        load()
+        import_ms = timed(load, max(steps, 3))
+        import_gbps = 2 * 2 * Kd.numel() * 2 / (import_ms * 1e-3) / 1e9      # K and V, read and written
+        run = (lambda: (load(), attend())) if with_import else attend
         run()
         torch.cuda.synchronize()
         err = ref = 0.0
-        rows = [0, 1, 15, 16, 17, 255, 256, 1023, S - 1]
+        rows = [i for i in (0, 1, 15, 16, 17, 255, 256, 1023, S - 1) if i < S]
         for (_, b, h) in units:                       # oracle on sampled rows of sampled (sequence, head) pairs
             Ku, Vu = kv[(layer, b, h)]
             for i in rows:
@@ -172,24 +194,21 @@ def prefill_bench(steps, warmup, tile):
             sys.exit("prefill output disagrees with the oracle: err %g, max expected %g" % (err, ref))
         for _ in range(warmup):
             run()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(steps):
-            run()
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / steps
+        ms = timed(run, steps)
+        attn_ms = timed(attend, steps) if with_import else ms
         pairs = wl.B * wl.Hq * (S * (S - 1) // 2)                  # (query, key) pairs below the diagonal
         flops = 4.0 * wl.D * pairs                                 # QK^T and PV, 2 flops per multiply-add
-        tflops = flops / (ms * 1e-3) / 1e12
+        tflops = flops / (attn_ms * 1e-3) / 1e12
         print(json.dumps({
-            "metric": "prompt-encoding attention, one condensed layer (Llama-7B shape, B=16, S=2048)",
+            "metric": "prompt-encoding attention%s, one condensed layer (Llama-7B shape, B=%d, S=%d)"
+                      % (" with the K/V import before it" if with_import else "", B, S),
             "value": wl.B * S / (ms * 1e-3), "unit": "prompt tokens/s per layer", "n_gpus": 1, "steps": steps,
             "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": wl.name},
             "roofline": {"bound": "mfma", "kernel": "prefill_bf16_kernel", "achieved": tflops, "peak": 2500.0,
-                         "unit": "TFLOP/s", "frac": tflops / 2500.0, "traffic": None},
+                         "unit": "TFLOP/s", "frac": tflops / 2500.0, "traffic": None, "avg_launch_ms": attn_ms},
+            "import": {"kernel": "load_dense_bf16_kernel", "ms": import_ms, "read_plus_write_GBps": import_gbps,
+                       "frac_of_hbm_peak": import_gbps / HBM_PEAK_GBPS, "in_timed_step": bool(with_import)},
             "max_abs_err_vs_oracle": err, "max_abs_expected": ref}))
 
 
@@ -299,6 +318,10 @@ def main():
     ap.add_argument("--prefill", action="store_true",
                     help="instead of the decode benchmark: prompt-encoding attention of one layer (MFMA-bound)")
     ap.add_argument("--prefill-tile", type=int, default=0, help="query blocks per wave in the prefill kernel (2|4)")
+    ap.add_argument("--with-import", action="store_true",
+                    help="--prefill: a step is the K/V import (lckv_cache_load_dense) plus the attention that reads it")
+    ap.add_argument("--prompt-len", type=int, default=2048, help="--prefill: tokens per prompt")
+    ap.add_argument("--prompts", type=int, default=16, help="--prefill: prompts in the batch")
     ap.add_argument("--project", action="store_true",
                     help="instead of the decode benchmark: the q/k/v projections of one decode step (HBM-bound)")
     ap.add_argument("--batch", type=int, default=128, help="sequences in --project")
@@ -310,7 +333,8 @@ def main():
     if args.residency_sweep:
         return residency_sweep(args.steps, args.warmup)
     if args.prefill:
-        return prefill_bench(args.steps, args.warmup, args.prefill_tile)
+        return prefill_bench(args.steps, args.warmup, args.prefill_tile, args.with_import, args.prompt_len,
+                             args.prompts)
     if args.project:
         return project_bench(args.steps, args.warmup, args.batch, args.graph)
 
@@ -435,6 +459,7 @@ def main():
             "slots": sess.n_slots, "cache_GiB": round(sess.cache_bytes / 2 ** 30, 2)},
         "step_effective_GBps": step_gbps, "step_pct_of_hbm_peak": 100.0 * step_gbps / HBM_PEAK_GBPS,
         "read_probe_GBps": probe_gbps,
+        "cache_fill_import_GBps": [round(x, 1) for x in sess.import_GBps],   # lckv_cache_load_dense, read + write
         "roofline": {"bound": "hbm", "kernel": "attn_%s_kernel" % ("bf16" if wl.dtype == "bf16" else "f32"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": traffic, "launches": n_launch, "avg_launch_ms": avg_kernel_ms,

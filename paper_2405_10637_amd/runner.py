@@ -44,6 +44,7 @@ class DecodeSession:
         self.lens = torch.from_numpy(self.lens0).to(DEV)
         self.max_len = int(self.lens0.max())
         self.steps_left = room
+        self.import_GBps = []     # read + write rate of each lckv_cache_load_dense call made by fill()
         ws = max(lk.lckv_workspace_bytes(self.h, wl.B, self.max_len + i) for i in range(room + 1))
         self.workspace = torch.empty(max(ws, 256), dtype=torch.uint8, device=DEV)
 
@@ -78,7 +79,13 @@ class DecodeSession:
             Vd = torch.empty(shape, dtype=wl.torch_dtype, device=DEV)
             synth.fill_normal_(Kd, wl.sigma, wl.seed * 31 + 2 * s)
             synth.fill_normal_(Vd, wl.sigma, wl.seed * 31 + 2 * s + 1)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
             lk.lckv_cache_load_dense(self.h, s, Kd, Vd, self.lens, wl.B, T)
+            e1.record()
+            e1.synchronize()
+            moved = 2 * 2 * int(self.lens0.astype(np.int64).sum()) * wl.Hkv * wl.D * wl.elem_bytes  # read + written
+            self.import_GBps.append(moved / (e0.elapsed_time(e1) * 1e-3) / 1e9)
             for (l, b, h) in by_slot.get(s, []):
                 n = int(self.lens0[b])
                 got[(l, b, h)] = (Kd[b, :n, h // G].float().cpu().numpy(), Vd[b, :n, h // G].float().cpu().numpy())
