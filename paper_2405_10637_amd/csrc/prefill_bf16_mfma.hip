@@ -4,16 +4,25 @@
 // masked, the slot holds the top layer's K/V of the previous iteration) or j <= i (warmup layer, the slot holds
 // this iteration's own K/V).
 //
-// Same matrix tiles and page layout as the decode kernel, but the 16 columns of a tile are 16 consecutive query
-// positions of one head instead of the heads of a group, and each column has its own number of visible keys:
-//   S^T[key][pos] = K_page . Q^T       (v_mfma_f32_16x16x32_bf16)
-//   O^T[d][pos]  += V_pages^T . P^T    (v_mfma_f32_16x16x32_bf16 over two pages = 32 keys at a time)
-// A workgroup of 4 waves owns 4 * QB blocks of 16 positions of one head (QB per wave) and walks the key pages
-// 0 .. diagonal once.  Pages are brought into LDS by direct global-to-LDS loads (global_load_lds_dwordx4; the
-// cache stores pages in operand order, so the LDS image needs no rearrangement and every wave reads its operands
-// with conflict-free ds_read_b128), ST tiles of NPG pages in flight, and every page feeds all 64 * QB queries of
-// the workgroup.  No merge between waves.  Compute-bound; the K/V of a head (S * D * 4 bytes) stay in the L2 of
-// the XCD that runs all row chunks of that head.
+// Same page layout as the decode kernel, but here the columns of a matrix tile are 32 consecutive query positions
+// of one head, each with its own number of visible keys, and the tiles are 32 x 32:
+//   S^T[32 keys][32 queries]  = K_pair[32 keys x D] . Q^T[D x 32 queries]       v_mfma_f32_32x32x16_bf16, D/16 steps
+//   O^T[32 d][32 queries]    += V_page^T[32 d x 16 keys] . P^T[16 keys x 32 queries]   same instruction, per page
+// With the 32 x 32 accumulator layout a lane holds 16 scores of ONE query (and lane + 32 the other 16): the running
+// maximum and the row sum need a single v_permlane32_swap, and the 8 probabilities a lane packs per page are
+// exactly the B operand of the P.V instruction of that page.  The V operand of that instruction - for the lane of
+// channel d and half h: positions 4h..4h+3 and 8+4h..8+4h+3 of the page - is two 8-byte pieces 512 bytes apart in
+// the page as stored, one two-address LDS read, no register shuffling.
+// A workgroup of 4 waves owns 4 * QT * 32 positions of one head (QT tiles of 32 per wave) and walks the key pages
+// 0 .. diagonal once, two pages (32 keys) at a time.  Pages are brought into LDS by direct global-to-LDS loads
+// (global_load_lds_dwordx4; the cache stores pages in operand order, so the LDS image needs no rearrangement and
+// every operand read is conflict-free), ST tiles of NPG pages in flight, and every page feeds all queries of the
+// workgroup.  A wave's tiles that lie wholly below its first row go through a loop without masks; only the tiles
+// the diagonal (or the end of the prompt) crosses pay for masking, in a second loop that shares the accumulators.
+// No merge between waves.  Compute-bound; the K/V of a head (S * D * 4 bytes) stay in the L2 of the XCD that runs
+// all row chunks of that head.
+#include <type_traits>
+
 #include "bf16_mfma_common.h"
 
 namespace lckv {
@@ -22,17 +31,23 @@ namespace {
 
 typedef __attribute__((address_space(3))) void *LdsPtr;
 typedef __attribute__((address_space(4))) const int32_t *ConstTablePtr;
+typedef __attribute__((ext_vector_type(16))) float floatx16;
 
-template <int D, int QB, int NPG, int ST, bool PAGED>
-__global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void prefill_bf16_kernel(AttnParams p, int S, int heads_per_group) {
+#ifndef LCKV_PF_OCC
+#define LCKV_PF_OCC 3
+#endif
+template <int D, int QT, int NPG, int ST, bool PAGED>
+__global__ __launch_bounds__(256, (D * QT <= 128 ? LCKV_PF_OCC : 1)) void prefill_bf16_kernel(
+    AttnParams p, int S, int heads_per_group) {
     // (waves per SIMD the register budget is cut for: within a wave the score products, the softmax and the P.V
     //  products run one after the other, so it is the other waves of the SIMD that keep the matrix core busy
-    //  meanwhile - 3 waves at 2 query blocks per wave measured faster than 2 waves with more registers each; the
-    //  128-channel, 4-block shape needs 128 registers for its accumulators alone)
-    constexpr int kRows = 16 * QB;                 // query positions per wave
+    //  meanwhile)
+    constexpr int kRows = 32 * QT;                 // query positions per wave
     constexpr int kPair = 2 * kPage * D * 2;       // bytes of a K page + V page
     constexpr int kLoadsPerPage = kPair / 1024;    // 1 KiB per wave-wide load
     constexpr int kLoadsPerWave = NPG * kLoadsPerPage / 4;
+    constexpr int kSteps = D / 16;                 // matrix instructions per score tile
+    constexpr int kDT = D / 32;                    // 32-channel tiles of the output
     static_assert(NPG * kLoadsPerPage % 4 == 0, "a tile's loads must divide among the four waves");
     static_assert(NPG % 2 == 0, "pages are consumed in pairs");
     constexpr float kLazy = 8.f;
@@ -59,24 +74,24 @@ __global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void pre
     const int h = unit % p.Hq, b = unit / p.Hq;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int c = lane & 15, kb = lane >> 4;  // query position within a block / key quad
+    const int c = lane & 31, hf = lane >> 5;  // query position within a tile / which half of the key octets
     const int g = h / p.G;
     const int i_wg = chunk * 4 * kRows;       // first row of the workgroup
     const int i_lo = i_wg + wave * kRows;     // first row of this wave
 
     // Q^T operands first: their addresses need nothing that is loaded, so they travel while the prompt length
     // and the first tiles are fetched (rows past the prompt are read too - they exist - and not used); they are
-    // waited for just before the loop.
-    bf16x8 qb[QB][D / 32];
+    // waited for just before the loop.  Lane (c, hf) holds channels 16 s + 8 hf .. + 7 of query i_lo + 32 x + c.
+    bf16x8 qb[QT][kSteps];
 #pragma unroll
-    for (int x = 0; x < QB; ++x) {
-        const int i = i_lo + 16 * x + c;
-        const char *qp = (const char *)p.q + ((((int64_t)b * S + i) * p.Hq + h) * D + kb * 8) * 2;
+    for (int x = 0; x < QT; ++x) {
+        const int i = i_lo + 32 * x + c;
+        const char *qp = (const char *)p.q + ((((int64_t)b * S + i) * p.Hq + h) * D + hf * 8) * 2;
 #pragma unroll
-        for (int ks = 0; ks < D / 32; ++ks) {
+        for (int s = 0; s < kSteps; ++s) {
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (i < S) v = *(const u32x4 *)(qp + ks * 64);
-            qb[x][ks] = __builtin_bit_cast(bf16x8, v);
+            if (i < S) v = *(const u32x4 *)(qp + s * 32);
+            qb[x][s] = __builtin_bit_cast(bf16x8, v);
         }
     }
     int len = ((ConstTablePtr)p.seq_lens)[b];  // a scalar load (the lengths are not written while the kernel runs)
@@ -97,23 +112,26 @@ __global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void pre
     }
     if (i_wg >= len) return;  // uniform over the workgroup: nothing to attend
 
-    int n_col[QB];          // the number of keys each column sees
+    int n_col[QT];          // the number of keys each column sees
 #pragma unroll
-    for (int x = 0; x < QB; ++x) n_col[x] = min(i_lo + 16 * x + c + self, len);
-    floatx4 acc[QB][D / 16];
-    float m[QB], l[QB];
+    for (int x = 0; x < QT; ++x) n_col[x] = min(i_lo + 32 * x + c + self, len);
+    floatx16 acc[QT][kDT];
+    float m[QT], l[QT];
 #pragma unroll
-    for (int x = 0; x < QB; ++x) {
+    for (int x = 0; x < QT; ++x) {
         m[x] = kNegInf;
         l[x] = 0.f;
 #pragma unroll
-        for (int j = 0; j < D / 16; ++j) acc[x][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < kDT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[x][j][e] = 0.f;
     }
     const float cs = p.scale_log2e;
     const int lane_off = lane * 16;
-    // pages needed by the workgroup (its last row) and by this wave
+    // pages needed by the workgroup (its last row) and by this wave; keys every row of this wave sees
     const int n_pages_wg = (min(i_wg + 4 * kRows - 1 + self, len) + kPage - 1) / kPage;
     const int n_pages = active ? (min(i_lo + kRows - 1 + self, len) + kPage - 1) / kPage : 0;
+    const int n_plain = active ? min(i_lo + self, len) : 0;  // keys [0, n_plain) are visible to all of the wave's rows
     const int n_tiles = (n_pages_wg + NPG - 1) / NPG;
 
     // This wave's share of the loads of tile t: 1 KiB pieces wave, wave + 4, ... of the tile's NPG page pairs.
@@ -151,63 +169,53 @@ __global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void pre
         }
     };
 
-    // Two consecutive pages (32 keys) at a time: one softmax update per 32 keys, and the P.V product runs on the
-    // full-rate 16x16x32 instruction - its 8 keys per lane are this lane's 4 keys of the first page and its 4
-    // keys of the second, which is how the two score tiles and the two V operands already sit in registers.
-    // `second` (wave-uniform) is false when the pair's second page lies above this wave's diagonal.
-    // In three phases (scores of all QB blocks, softmax, P.V of all blocks) so that the K operands and the V
-    // operands are not live in registers at the same time.
-    auto consume_pair = [&](const char *page0, int pg, bool second) {
-        const char *page1 = page0 + kPair;
-        floatx4 z0[QB], z1[QB];
-        bool live[QB];  // wave-uniform: the block sees at least one key of the pair
-        {
-            u32x4 kr[D / 32];
+    // Where this lane's operands sit in a page pair held in LDS (bytes from the pair's first page).
+    //   K operand of step s (channels 16 s .. 16 s + 15, A operand: lane (key, hf) holds channels 16 s + 8 hf .. + 7
+    //   of key `key` of the 32): the K page stores 16-byte chunks [channel octet][position]; octet 2 s + hf of
+    //   position c % 16 of page c / 16.
+    //   V operand of channel tile dt for one page (A operand: lane (d, hf) holds 8 positions of channel 32 dt + d):
+    //   positions 4 hf .. 4 hf + 3 at quad hf and 8 + 4 hf .. at quad hf + 2 of the V page's
+    //   [channel pair][quad][16 channels][2][4 positions] order - 8 bytes each, 512 bytes apart.
+    const int k_lane = (c >> 4) * kPair + (hf * kPage + (c & 15)) * 16;
+    const int v_lane = kPair / 2 + ((hf * 16 + (c & 15)) * 2 + (c >> 4)) * 8;
+
+    // One pair of pages (32 keys) against the wave's QT tiles of 32 queries.  DIAG = false: every key of the pair
+    // is visible to every row of the wave - no masks.  DIAG = true: the diagonal or the end of the prompt crosses
+    // the pair: scores are masked per column, and values at positions past the prompt are cleared (they may hold
+    // anything, 0 * NaN would poison the sum).
+    auto consume_pair = [&](const char *pair, int pg, auto diag_tag) {
+        constexpr bool DIAG = decltype(diag_tag)::value;
+        floatx16 z[QT];
 #pragma unroll
-            for (int ks = 0; ks < D / 32; ++ks) kr[ks] = *(const u32x4 *)(page0 + ks * 1024 + lane_off);
+        for (int x = 0; x < QT; ++x)
 #pragma unroll
-            for (int x = 0; x < QB; ++x) {
-                const int n_hi = min(i_lo + 16 * x + 15 + self, len);  // keys the last column of the block sees
-                live[x] = pg * kPage < n_hi;
-                z0[x] = floatx4{0.f, 0.f, 0.f, 0.f};
-                z1[x] = floatx4{kNegInf, kNegInf, kNegInf, kNegInf};
-                if (!live[x]) continue;
+            for (int e = 0; e < 16; ++e) z[x][e] = 0.f;
 #pragma unroll
-                for (int ks = 0; ks < D / 32; ++ks)
-                    z0[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[ks]), qb[x][ks],
-                                                                    z0[x], 0, 0, 0);
-            }
-            if (second) {
+        for (int s = 0; s < kSteps; ++s) {
+            const u32x4 kr = *(const u32x4 *)(pair + k_lane + s * 512);
 #pragma unroll
-                for (int ks = 0; ks < D / 32; ++ks) kr[ks] = *(const u32x4 *)(page1 + ks * 1024 + lane_off);
-#pragma unroll
-                for (int x = 0; x < QB; ++x) {
-                    const int n_hi = min(i_lo + 16 * x + 15 + self, len);
-                    if ((pg + 1) * kPage >= n_hi) continue;  // the second page lies above this block's diagonal
-                    z1[x] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int ks = 0; ks < D / 32; ++ks)
-                        z1[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[ks]), qb[x][ks],
-                                                                        z1[x], 0, 0, 0);
-                }
-            }
+            for (int x = 0; x < QT; ++x)
+                z[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kr), qb[x][s], z[x], 0, 0, 0);
         }
-        bf16x8 pb[QB];
+        bf16x8 pb[QT][2];
 #pragma unroll
-        for (int x = 0; x < QB; ++x) {
-            if (!live[x]) continue;
-            const int n_lo = min(i_lo + 16 * x + self, len);  // keys the first column of the block sees
-            if ((pg + 2) * kPage > n_lo) {                    // the diagonal crosses this pair: mask per column
-                const int key0 = pg * kPage + 4 * kb;
+        for (int x = 0; x < QT; ++x) {
+            // score register e of this lane: key pg * 16 + 8 (e / 4) + 4 hf + e % 4 of query column c
+            if (DIAG) {
+                const int key0 = pg * kPage + 4 * hf;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (key0 + e >= n_col[x]) z0[x][e] = kNegInf;
-                    if (key0 + kPage + e >= n_col[x]) z1[x][e] = kNegInf;
-                }
+                for (int e = 0; e < 16; ++e)
+                    if (key0 + 8 * (e >> 2) + (e & 3) >= n_col[x]) z[x][e] = kNegInf;
             }
-            float smax = fmaxf(fmaxf(fmaxf(z0[x][0], z0[x][1]), fmaxf(z0[x][2], z0[x][3])),
-                               fmaxf(fmaxf(z1[x][0], z1[x][1]), fmaxf(z1[x][2], z1[x][3])));
-            smax = column_max4(smax);
+            float smax = fmaxf(fmaxf(z[x][0], z[x][1]), z[x][2]);
+#pragma unroll
+            for (int e = 3; e < 15; e += 2) smax = fmaxf(fmaxf(smax, z[x][e]), z[x][e + 1]);
+            smax = fmaxf(smax, z[x][15]);
+            {   // the two lanes of a column (c and c + 32) share one running maximum
+                float a = smax, bb = smax;
+                swap_halves32(a, bb);
+                smax = fmaxf(a, bb);
+            }
             // The running reference m[x] follows the true maximum lazily: the accumulators are rescaled only when
             // some column's maximum has outgrown its reference by more than 2^kLazy (or has no reference yet), so
             // the weights stay <= 2^kLazy - harmless in fp32 sums and at bf16's relative precision - and the result
@@ -218,48 +226,50 @@ __global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void pre
                 m[x] = m_new;
                 l[x] *= alpha;
 #pragma unroll
-                for (int j = 0; j < D / 16; ++j) acc[x][j] *= alpha;
+                for (int j = 0; j < kDT; ++j) acc[x][j] *= alpha;
             }
             const float mb = (m[x] == kNegInf ? 0.f : m[x]) * cs;
-            float pr[8];
+            float pr[16];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                pr[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(z0[x][e], cs, -mb));
-                pr[4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(z1[x][e], cs, -mb));
+            for (int e = 0; e < 16; ++e) pr[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(z[x][e], cs, -mb));
+#pragma unroll
+            for (int pgi = 0; pgi < 2; ++pgi) {
+                const float *q8 = pr + 8 * pgi;
+                const u32x4 pk = {pack_bf16(q8[0], q8[1]), pack_bf16(q8[2], q8[3]), pack_bf16(q8[4], q8[5]),
+                                  pack_bf16(q8[6], q8[7])};
+                pb[x][pgi] = __builtin_bit_cast(bf16x8, pk);
             }
-            const u32x4 pk = {pack_bf16(pr[0], pr[1]), pack_bf16(pr[2], pr[3]), pack_bf16(pr[4], pr[5]),
-                              pack_bf16(pr[6], pr[7])};
-            pb[x] = __builtin_bit_cast(bf16x8, pk);
-            l[x] += ((pr[0] + pr[1]) + (pr[2] + pr[3])) + ((pr[4] + pr[5]) + (pr[6] + pr[7]));
+            l[x] += (((pr[0] + pr[1]) + (pr[2] + pr[3])) + ((pr[4] + pr[5]) + (pr[6] + pr[7]))) +
+                    (((pr[8] + pr[9]) + (pr[10] + pr[11])) + ((pr[12] + pr[13]) + (pr[14] + pr[15])));
         }
-        uint32_t a01 = 0xffffffffu, a23 = 0xffffffffu, b01 = 0xffffffffu, b23 = 0xffffffffu;
-        if ((pg + 2) * kPage > len) {  // the prompt ends inside this pair: clear stale values (0 * NaN)
-            const int nv0 = len - (pg * kPage + 4 * kb), nv1 = nv0 - kPage;
-            a01 = nv0 >= 2 ? 0xffffffffu : (nv0 == 1 ? 0x0000ffffu : 0u);
-            a23 = nv0 >= 4 ? 0xffffffffu : (nv0 == 3 ? 0x0000ffffu : 0u);
-            b01 = nv1 >= 2 ? 0xffffffffu : (nv1 == 1 ? 0x0000ffffu : 0u);
-            b23 = nv1 >= 4 ? 0xffffffffu : (nv1 == 3 ? 0x0000ffffu : 0u);
-        }
-        if (!second) b01 = b23 = 0u;  // that LDS page holds nothing of this wave's
-        const bool clear_stale = (pg + 2) * kPage > len || !second;
 #pragma unroll
-        for (int dp = 0; dp < D / 32; ++dp) {
-            const u32x4 v0 = *(const u32x4 *)(page0 + kPair / 2 + dp * 1024 + lane_off);
-            const u32x4 v1 = *(const u32x4 *)(page1 + kPair / 2 + dp * 1024 + lane_off);
-            u32x4 lo = {v0[0], v0[1], v1[0], v1[1]};  // channel block 2dp, 8 keys
-            u32x4 hi = {v0[2], v0[3], v1[2], v1[3]};  // channel block 2dp + 1
-            if (clear_stale) {                        // wave-uniform, true only for a wave's last pairs
-                const u32x4 keep = {a01, a23, b01, b23};
-                lo &= keep;
-                hi &= keep;
+        for (int pgi = 0; pgi < 2; ++pgi) {
+            uint32_t k01 = 0xffffffffu, k23 = 0xffffffffu, k45 = 0xffffffffu, k67 = 0xffffffffu;
+            bool clear_stale = false;
+            if (DIAG) {
+                clear_stale = (pg + pgi + 1) * kPage > len;  // wave-uniform: the prompt ends inside this page
+                if (clear_stale) {
+                    const int nv0 = len - ((pg + pgi) * kPage + 4 * hf), nv1 = nv0 - 8;  // valid among each four
+                    k01 = nv0 >= 2 ? 0xffffffffu : (nv0 == 1 ? 0x0000ffffu : 0u);
+                    k23 = nv0 >= 4 ? 0xffffffffu : (nv0 == 3 ? 0x0000ffffu : 0u);
+                    k45 = nv1 >= 2 ? 0xffffffffu : (nv1 == 1 ? 0x0000ffffu : 0u);
+                    k67 = nv1 >= 4 ? 0xffffffffu : (nv1 == 3 ? 0x0000ffffu : 0u);
+                }
             }
 #pragma unroll
-            for (int x = 0; x < QB; ++x) {
-                if (!live[x]) continue;
-                acc[x][2 * dp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lo), pb[x],
-                                                                         acc[x][2 * dp], 0, 0, 0);
-                acc[x][2 * dp + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, hi), pb[x],
-                                                                             acc[x][2 * dp + 1], 0, 0, 0);
+            for (int dt = 0; dt < kDT; ++dt) {
+                const char *vp = pair + pgi * kPair + v_lane + dt * 1024;
+                const u32x2 lo = *(const u32x2 *)vp;
+                const u32x2 hi = *(const u32x2 *)(vp + 512);
+                u32x4 vr = {lo[0], lo[1], hi[0], hi[1]};
+                if (DIAG && clear_stale) {
+                    const u32x4 keep = {k01, k23, k45, k67};
+                    vr &= keep;
+                }
+#pragma unroll
+                for (int x = 0; x < QT; ++x)
+                    acc[x][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vr), pb[x][pgi],
+                                                                         acc[x][dt], 0, 0, 0);
             }
         }
     };
@@ -273,10 +283,10 @@ __global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void pre
     // The Q^T operands are waited for here, before the loop: a wait for them inside the loop would be a wait for
     // all loads in flight.
 #pragma unroll
-    for (int x = 0; x < QB; ++x)
+    for (int x = 0; x < QT; ++x)
 #pragma unroll
-        for (int ks = 0; ks < D / 32; ++ks) asm volatile("" ::"v"(qb[x][ks]));  // a use: the compiler waits here
-    for (int t = 0; t < n_tiles; ++t) {
+        for (int s = 0; s < kSteps; ++s) asm volatile("" ::"v"(qb[x][s]));  // a use: the compiler waits here
+    auto sync_tile = [&](int t) {
         const int later = min(ST - 2, n_tiles - 1 - t);  // tiles issued after tile t
         if (later <= 0)
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -287,34 +297,54 @@ __global__ __launch_bounds__(256, (QB <= 2 ? 3 : D * QB > 384 ? 1 : 2)) void pre
         // the bare barrier instruction: __syncthreads() comes with a fence that waits for ALL outstanding loads
         asm volatile("s_barrier" ::: "memory");
         if (t + ST - 1 < n_tiles) issue_tile(t + ST - 1);
+    };
+    // Two loops over the tiles, one after the other, sharing the accumulators: first the tiles all of whose keys
+    // every row of this wave sees (no masks), then the rest.  Every wave passes n_tiles barriers in all, wherever
+    // its own first loop ends.  (One loop with the choice inside made the compiler copy all accumulators between
+    // two register sets in every round.)
+    const int t_plain = min(n_tiles, n_plain / (NPG * kPage));  // tiles 0 .. t_plain - 1 lie below the wave's first row
+    int t = 0;
+    for (; t < t_plain; ++t) {
+        sync_tile(t);
+#pragma unroll
+        for (int j = 0; j < NPG; j += 2) consume_pair(&lds[t % ST][j * kPair], t * NPG + j, std::false_type{});
+    }
+    for (; t < n_tiles; ++t) {
+        sync_tile(t);
 #pragma unroll
         for (int j = 0; j < NPG; j += 2) {
             const int pg = t * NPG + j;
-            if (pg < n_pages) consume_pair(&lds[t % ST][j * kPair], pg, pg + 1 < n_pages);
+            if (pg < n_pages) consume_pair(&lds[t % ST][j * kPair], pg, std::true_type{});
         }
     }
     if (!active) return;
 
+    // O^T accumulator register e of channel tile dt: channel 32 dt + 8 (e / 4) + 4 hf + e % 4 of query column c
 #pragma unroll
-    for (int x = 0; x < QB; ++x) {
-        const float L = column_sum4(l[x]);
-        const int i = i_lo + 16 * x + c;
+    for (int x = 0; x < QT; ++x) {
+        float a = l[x], bb = l[x];
+        swap_halves32(a, bb);
+        const float L = a + bb;
+        const int i = i_lo + 32 * x + c;
         if (i >= S) continue;
         const float inv = (i < len && L > 0.f) ? 1.f / L : 0.f;  // rows past the prompt, and a token that sees
                                                                  // nothing (zero dummy K/V), are zero
-        uint16_t *o = out + (((int64_t)b * S + i) * p.Hq + h) * D + 4 * kb;
+        uint16_t *o = out + (((int64_t)b * S + i) * p.Hq + h) * D + 4 * hf;
 #pragma unroll
-        for (int j = 0; j < D / 16; ++j) {
-            const floatx4 a = acc[x][j];
-            u32x2 pk = {pack_bf16(a[0] * inv, a[1] * inv), pack_bf16(a[2] * inv, a[3] * inv)};
-            *(u32x2 *)(o + j * 16) = pk;
-        }
+        for (int dt = 0; dt < kDT; ++dt)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const floatx16 &a16 = acc[x][dt];
+                u32x2 pk = {pack_bf16(a16[4 * q4] * inv, a16[4 * q4 + 1] * inv),
+                            pack_bf16(a16[4 * q4 + 2] * inv, a16[4 * q4 + 3] * inv)};
+                *(u32x2 *)(o + dt * 32 + q4 * 8) = pk;
+            }
     }
 }
 
-template <int D, int QB, int NPG, int ST = 3>
-hipError_t launch_qb(const AttnParams &p, int S, hipStream_t s) {
-    const int rows_per_group = 4 * 16 * QB;
+template <int D, int QT, int NPG, int ST = 3>
+hipError_t launch_qt(const AttnParams &p, int S, hipStream_t s) {
+    const int rows_per_group = 4 * 32 * QT;
     const int n_chunks = (S + rows_per_group - 1) / rows_per_group;
     const int64_t units = (int64_t)p.Hq * p.B, units_per_xcd = (units + 7) / 8;
     const int heads_per_group = 8;  // measured on the Llama-7B shape: 1: 648, 2: 671, 4: 685, 8: 693, 16: 670 TFLOP/s
@@ -322,19 +352,20 @@ hipError_t launch_qb(const AttnParams &p, int S, hipStream_t s) {
     if (per_xcd * 8 > (int64_t)1 << 30) return hipErrorInvalidValue;
     dim3 grid((unsigned)(per_xcd * 8)), block(256);  // one task per workgroup, the same number for each of the 8 XCDs
     if (p.slot.table)
-        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, NPG, ST, true>), grid, block, 0, s, p, S, heads_per_group);
+        hipLaunchKernelGGL((prefill_bf16_kernel<D, QT, NPG, ST, true>), grid, block, 0, s, p, S, heads_per_group);
     else
-        hipLaunchKernelGGL((prefill_bf16_kernel<D, QB, NPG, ST, false>), grid, block, 0, s, p, S, heads_per_group);
+        hipLaunchKernelGGL((prefill_bf16_kernel<D, QT, NPG, ST, false>), grid, block, 0, s, p, S, heads_per_group);
     return hipGetLastError();
 }
 
 }  // namespace
 
 // p: seq_lens = prompt lengths, max_n = min(S, capacity), self_visible, scale; no splits.
+// qb: 16-position query blocks per wave, 2 (one 32-query tile) or 4 (two); 0 = default.
 hipError_t launch_prefill_bf16(const AttnParams &p, int S, int D, int qb, hipStream_t s) {
-    if (qb == 0) qb = 2;  // measured: 643 vs 284 TFLOP/s at D=128 (Llama-7B shape), 543 vs 509 at D=64 (TinyLlama shape)
-    if (D == 128) return qb == 2 ? launch_qb<128, 2, 2>(p, S, s) : launch_qb<128, 4, 2>(p, S, s);
-    return qb == 2 ? launch_qb<64, 2, 4>(p, S, s) : launch_qb<64, 4, 4>(p, S, s);
+    if (qb == 0) qb = 2;
+    if (D == 128) return qb == 2 ? launch_qt<128, 1, 2>(p, S, s) : launch_qt<128, 2, 2>(p, S, s);
+    return qb == 2 ? launch_qt<64, 1, 4>(p, S, s) : launch_qt<64, 2, 4>(p, S, s);
 }
 
 }  // namespace lckv

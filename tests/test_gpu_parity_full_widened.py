@@ -1,6 +1,6 @@
 """GPU parity of the widened path at the sizes bench.py times it at, on sampled outputs the oracle computes one by
 one: the prompt-encoding attention (Llama-7B shape, 16 prompts of 2048 tokens, a condensed and a warmup layer,
-ragged prompt lengths) and the projections of a decode step (Llama-7B shape, hidden 4096, B = 128: a layer without
+ragged prompt lengths; 2 prompts of 16384 tokens, contiguous and paged; TinyLlama shape with D = 64 at 2048 tokens) and the projections of a decode step (Llama-7B shape, hidden 4096, B = 128: a layer without
 K/V projections and the three producing layers, with the keys and values read back from the cache)."""
 import numpy as np
 import pytest
@@ -44,6 +44,54 @@ def test_prefill_attention_at_bench_size_sampled_rows():
                 rows = sorted({0, 1, 15, 16, 17, 31, 32, 255, 1023, n_b - 1, min(n_b, S - 1), S - 1})
                 for i in rows:
                     if i >= n_b:                                        # rows past the prompt are exact zeros
+                        assert (out[b, i, h] == 0).all(), (layer, b, h, i)
+                        continue
+                    n = i + (1 if vis else 0)
+                    want.append(orc.attend(to_f32_numpy(q[b, i, h]), Ku[:n], Vu[:n], scale))
+                    got.append(out[b, i, h])
+            err = check_close(torch.stack(got), np.stack(want), wl.dtype, "%s layer %d" % (wl.name, layer))
+            print("  layer %d (self visible %d): %d rows, max-abs error %.3g" % (layer, vis, len(got), err), flush=True)
+        assert lk.lckv_last_device_error(sess.h) == 0
+
+
+@pytest.mark.parametrize("name,base,B,S,paged,tile", [
+    ("long prompts, Llama-7B shape", "C3", 2, 16384, False, 0),
+    ("long prompts, Llama-7B shape, paged", "C3", 2, 16384, True, 0),
+    ("TinyLlama shape (D=64, 8 query heads per kv head)", "C2", 8, 2048, False, 0),
+    ("TinyLlama shape, two query tiles per wave", "C2", 8, 2048, False, 4),
+])
+def test_prefill_attention_long_and_d64_sampled_rows(name, base, B, S, paged, tile):
+    # the sizes the long-prompt and the D = 64 throughput figures are quoted at: rows sampled across the prompt,
+    # at tile and workgroup edges, each compared with the oracle's definition on exactly the K/V rows it sees
+    wl = getattr(synth, base).with_(B=B, T=S, paged=paged, name="prefill-%s-B%d-S%d" % (base, B, S))
+    print("full-size case", name, wl.name, "tile", tile, flush=True)
+    with DecodeSession(wl, room=16) as sess:
+        if tile:
+            lk.lckv_set_prefill_tile(sess.h, tile)
+        lens = np.full(wl.B, S, np.int32)
+        lens[1] = S - 4097 if S > 8192 else 1000                        # one shorter prompt
+        dev_lens = torch.from_numpy(lens).cuda()
+        warm = [l for l in range(wl.L) if sess.kv_slot[l][1]][0]
+        cond = [l for l in range(wl.L) if not sess.kv_slot[l][1]][0]
+        units = [(layer, b, h) for layer in (cond, warm) for b in (0, 1) for h in (0, 5, wl.Hq - 1)]
+        kv = sess.fill(units)
+        q = synth._normal((wl.B, S, wl.Hq, wl.D), wl.sigma, wl.torch_dtype, wl.seed + 9, device="cuda")
+        scale = 1.0 / np.sqrt(wl.D)
+        for layer in (cond, warm):
+            vis = sess.kv_slot[layer][1]
+            out = torch.full_like(q, float("nan"))
+            lk.lckv_prefill_attention(sess.h, layer, q, out, dev_lens, wl.B, S)
+            torch.cuda.synchronize()
+            got, want = [], []
+            for (l, b, h) in units:
+                if l != layer:
+                    continue
+                Ku, Vu = kv[(l, b, h)]
+                n_b = int(lens[b])
+                rows = sorted({0, 1, 31, 32, 33, 127, 128, 129, 255, 256, 1023, S // 2 - 1, S // 2, n_b - 33, n_b - 32,
+                               n_b - 1, min(n_b, S - 1), S - 1})
+                for i in rows:
+                    if i >= n_b:
                         assert (out[b, i, h] == 0).all(), (layer, b, h, i)
                         continue
                     n = i + (1 if vis else 0)
