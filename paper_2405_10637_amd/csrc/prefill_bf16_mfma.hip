@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256, (D * QT <= 128 ? LCKV_PF_OCC : 1)) void prefil
     static_assert(NPG * kLoadsPerPage % 4 == 0, "a tile's loads must divide among the four waves");
     static_assert(NPG % 2 == 0, "pages are consumed in pairs");
     constexpr float kLazy = 8.f;
-    static_assert(ST >= 2 && ST <= 4, "tiles in flight");
+    static_assert(ST >= 3 && ST <= 4, "tiles in flight (the staging areas of the prologue and epilogue need a third buffer)");
     __shared__ __attribute__((aligned(16))) char lds[ST][NPG * kPair];
 
     // Which (sequence, head, row chunk) this workgroup takes.  Workgroups are handed to the 8 XCDs round-robin
@@ -79,21 +79,24 @@ __global__ __launch_bounds__(256, (D * QT <= 128 ? LCKV_PF_OCC : 1)) void prefil
     const int i_wg = chunk * 4 * kRows;       // first row of the workgroup
     const int i_lo = i_wg + wave * kRows;     // first row of this wave
 
-    // Q^T operands first: their addresses need nothing that is loaded, so they travel while the prompt length
-    // and the first tiles are fetched (rows past the prompt are read too - they exist - and not used); they are
-    // waited for just before the loop.  Lane (c, hf) holds channels 16 s + 8 hf .. + 7 of query i_lo + 32 x + c.
-    bf16x8 qb[QT][kSteps];
+    // The queries first: their addresses need nothing that is loaded, so they travel while the prompt length and
+    // the first tiles are fetched.  They are fetched in 128-byte half rows, 8 rows per instruction (whole cache
+    // lines; fetching them in operand order would take 32 bytes of 32 different rows per instruction, which
+    // measured 11 us per workgroup), and turned into operand order through LDS further down.  Rows past the end
+    // of the tensor read the last row and are never stored.
+    constexpr int kHalves = D / 64;            // 128-byte pieces of a query row
+    u32x4 qraw[QT][kHalves][4];
+    bf16x8 qb[QT][kSteps];                     // the operands made of them before the loop
 #pragma unroll
-    for (int x = 0; x < QT; ++x) {
-        const int i = i_lo + 32 * x + c;
-        const char *qp = (const char *)p.q + ((((int64_t)b * S + i) * p.Hq + h) * D + hf * 8) * 2;
+    for (int x = 0; x < QT; ++x)
 #pragma unroll
-        for (int s = 0; s < kSteps; ++s) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (i < S) v = *(const u32x4 *)(qp + s * 32);
-            qb[x][s] = __builtin_bit_cast(bf16x8, v);
-        }
-    }
+        for (int hv = 0; hv < kHalves; ++hv)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int i = min(i_lo + 32 * x + 8 * k + (lane >> 3), S - 1);
+                const char *qp = (const char *)p.q + ((((int64_t)b * S + i) * p.Hq + h) * D) * 2;
+                qraw[x][hv][k] = *(const u32x4 *)(qp + hv * 128 + (lane & 7) * 16);
+            }
     int len = ((ConstTablePtr)p.seq_lens)[b];  // a scalar load (the lengths are not written while the kernel runs)
     if (len > p.max_n) {
         len = p.max_n;
@@ -280,8 +283,35 @@ __global__ __launch_bounds__(256, (D * QT <= 128 ? LCKV_PF_OCC : 1)) void prefil
     // later tiles have" means tile t is there) and every wave has finished reading tile t-1, whose buffer the
     // loads of tile t+ST-1 then overwrite.
     for (int t = 0; t < ST - 1 && t < n_tiles; ++t) issue_tile(t);
-    // The Q^T operands are waited for here, before the loop: a wait for them inside the loop would be a wait for
-    // all loads in flight.
+    // Q^T operands: lane (c, hf) holds channels 16 s + 8 hf .. + 7 of query i_lo + 32 x + c.  Each wave turns its
+    // half rows around in a 4 KiB piece of the last tile buffer, which no load targets before the first barrier:
+    // 32 rows of 128 bytes, the 16-byte chunks of a row exchanged by the row number (chunk ^ row % 8) so that
+    // neither the row-wise writes nor the column-wise reads pile up on a bank.  Wave-private, hence no barrier;
+    // the reads are waited for here, before the loop (a wait inside the loop would be a wait for all loads in
+    // flight).
+    {
+        static_assert(4 * 32 * 128 <= NPG * kPair, "the staging area is one tile buffer");
+        char *stage = &lds[ST - 1][wave * 4096];
+#pragma unroll
+        for (int x = 0; x < QT; ++x)
+#pragma unroll
+            for (int hv = 0; hv < kHalves; ++hv) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int row = 8 * k + (lane >> 3);
+                    *(u32x4 *)(stage + row * 128 + (((lane & 7) ^ (row & 7)) * 16)) = qraw[x][hv][k];
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4) {
+                    const u32x4 v = *(const u32x4 *)(stage + c * 128 + (((2 * s4 + hf) ^ (c & 7)) * 16));
+                    qb[x][hv * 4 + s4] = __builtin_bit_cast(bf16x8, v);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
+    }
 #pragma unroll
     for (int x = 0; x < QT; ++x)
 #pragma unroll
@@ -319,17 +349,22 @@ __global__ __launch_bounds__(256, (D * QT <= 128 ? LCKV_PF_OCC : 1)) void prefil
     }
     if (!active) return;
 
-    // O^T accumulator register e of channel tile dt: channel 32 dt + 8 (e / 4) + 4 hf + e % 4 of query column c
+    // O^T accumulator register e of channel tile dt: channel 32 dt + 8 (e / 4) + 4 hf + e % 4 of query column c.
+    // The rounded rows are turned around in LDS (a piece of the tile buffers that nobody reads any more: not the
+    // last tile's, which a slower wave may still be consuming) so that they leave as whole 2 D-byte rows, several
+    // rows per store instruction, instead of 8-byte pieces of 32 different rows.
+    constexpr int kRowBytes = D * 2, kCpr = D / 8;          // 16-byte chunks per row
+    constexpr int kStage = 32 * kRowBytes, kBuf = NPG * kPair;
+    static_assert(kBuf % kStage == 0 && 4 * kStage <= 2 * kBuf, "staging areas of the four waves fit two buffers");
+    char *stage = &lds[(n_tiles + (wave * kStage) / kBuf) % ST][(wave * kStage) % kBuf];
 #pragma unroll
     for (int x = 0; x < QT; ++x) {
         float a = l[x], bb = l[x];
         swap_halves32(a, bb);
         const float L = a + bb;
         const int i = i_lo + 32 * x + c;
-        if (i >= S) continue;
         const float inv = (i < len && L > 0.f) ? 1.f / L : 0.f;  // rows past the prompt, and a token that sees
                                                                  // nothing (zero dummy K/V), are zero
-        uint16_t *o = out + (((int64_t)b * S + i) * p.Hq + h) * D + 4 * hf;
 #pragma unroll
         for (int dt = 0; dt < kDT; ++dt)
 #pragma unroll
@@ -337,8 +372,20 @@ __global__ __launch_bounds__(256, (D * QT <= 128 ? LCKV_PF_OCC : 1)) void prefil
                 const floatx16 &a16 = acc[x][dt];
                 u32x2 pk = {pack_bf16(a16[4 * q4] * inv, a16[4 * q4 + 1] * inv),
                             pack_bf16(a16[4 * q4 + 2] * inv, a16[4 * q4 + 3] * inv)};
-                *(u32x2 *)(o + dt * 32 + q4 * 8) = pk;
+                const int chunk = 4 * dt + q4;  // channels 8 chunk .. + 7; this lane's half: 4 hf .. + 3
+                *(u32x2 *)(stage + c * kRowBytes + ((chunk ^ (c & (kCpr - 1))) * 16) + 8 * hf) = pk;
             }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int k = 0; k < 32 * kCpr / 64; ++k) {
+            const int row = k * (64 / kCpr) + lane / kCpr, chunk = lane % kCpr;
+            const u32x4 v = *(const u32x4 *)(stage + row * kRowBytes + ((chunk ^ (row & (kCpr - 1))) * 16));
+            const int i_row = i_lo + 32 * x + row;
+            if (i_row < S) *(u32x4 *)(out + (((int64_t)b * S + i_row) * p.Hq + h) * D + chunk * 8) = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
