@@ -181,14 +181,16 @@ int lckv_prefill_attention(lckv_cache *cache, int32_t layer, const void *q, void
  * (LCKV_ERR_CONFIG).
  * rot_t is the rotary position embedding in the Llama convention (the paper trains Llama models and does not
  * restate it): within a head, channel i < D/2 is paired with channel i + D/2 and the pair is turned by the
- * angle t * rope_base^(-2i/D); rope_base <= 0 means no rotation.  Products are accumulated in fp32 (bf16
- * caches; the hidden dimension is cut into slices whose partial sums are added in a fixed order, so results do
- * not vary from run to run) or in fp64 (fp32 caches), rotated in fp32 and rounded once to the element type.
+ * angle t * rope_base^(-2i/D); rope_base <= 0 means no rotation.  Products are accumulated in fp32 (bf16 caches:
+ * one launch; the hidden dimension is cut in four whose sums are added in a fixed order, so results do not vary
+ * from run to run) or in fp64 (fp32 caches, the parity mode: two launches), rotated in fp32 and rounded once to
+ * the element type.
  * x: device [B][hidden] in the cache's element type; w_q (Hq*D rows), w_k, w_v (Hkv*D rows): device, PACKED by
  * lckv_pack_projection_weight, 16-byte aligned; bf16 needs hidden % 256 == 0.  w_k and w_v must both be given
  * for a producing layer (LCKV_ERR_NULL) and must both be NULL for any other (LCKV_ERR_NOT_PRODUCER: such
  * parameters do not exist).  q_out: device [B][Hq][D].  dev_seq_lens: read, not changed.  workspace: device,
- * 256-byte aligned, at least lckv_project_workspace_bytes; its contents need not be kept between calls.
+ * 256-byte aligned, at least lckv_project_workspace_bytes (0 for bf16 caches: then it may be NULL); its contents
+ * need not be kept between calls.
  * k_out / v_out on a layer that produces no slot: LCKV_ERR_NOT_PRODUCER.  Only enqueues. */
 int lckv_project_qkv(lckv_cache *cache, int32_t layer, const void *x, int32_t hidden, const void *w_q,
                      const void *w_k, const void *w_v, void *q_out, void *k_out, void *v_out,
@@ -196,10 +198,12 @@ int lckv_project_qkv(lckv_cache *cache, int32_t layer, const void *x, int32_t hi
                      size_t workspace_bytes, void *hip_stream);
 int lckv_project_workspace_bytes(const lckv_cache *cache, int32_t B, int32_t hidden, size_t *bytes);
 /* Weights are handed to lckv_project_qkv in the order the matrix instructions take them (made once, when the
- * model is loaded).  w: device [n_rows][hidden] row-major ("out features x in features"), n_rows % 16 == 0;
- * w_packed: device, same size, must not overlap w.  bf16: tiles of 16 rows, each tile
- * [hidden/32 steps][4 channel octets kb][16 rows r][8 channels] (lane kb*16 + r of a wave holds channels
- * 32*step + 8*kb .. +7 of row r), a tile's image contiguous; fp32: a plain copy.  Only enqueues. */
+ * model is loaded).  w: device [n_rows][hidden] row-major ("out features x in features"), n_rows a multiple of the
+ * head dimension D (whole heads); w_packed: device, same size, must not overlap w.  bf16: tiles of 16 rows, each
+ * tile [hidden/32 steps][4 channel octets kb][16 rows r][8 channels] (lane kb*16 + r of a wave holds channels
+ * 32*step + 8*kb .. +7 of the tile's row r), a tile's image contiguous; tile t holds, of head t / (D/16), the
+ * rows of 8 rotary pairs: r < 8: channel 8 (t % (D/16)) + r, r >= 8: its partner D/2 further on - so the
+ * rotation needs nothing outside one wave.  fp32: a plain copy.  Only enqueues. */
 int lckv_pack_projection_weight(const lckv_cache *cache, const void *w, void *w_packed, int32_t n_rows,
                                 int32_t hidden, void *hip_stream);
 

@@ -532,30 +532,25 @@ int lckv_workspace_bytes(const lckv_cache *c, int32_t B, int32_t max_len_hint, s
     return LCKV_OK;
 }
 
-// Workspace of lckv_project_qkv: fp32 partial sums [slices][B][rows], the larger of a producing layer's
-// (rows = (Hq + 2 Hkv) D) and a non-producing layer's (rows = Hq D, possibly cut into more slices).
+// Workspace of lckv_project_qkv: none for bf16 caches (one launch, sums stay on chip); fp32 caches (parity mode):
+// the products [B][(Hq + 2 Hkv) D] in fp32 between the two launches.
 static size_t project_acc_bytes(const lckv_cache *c, int B, int hidden) {
-    const size_t n_kv = ((size_t)c->cfg.Hq + 2 * (size_t)c->cfg.Hkv) * c->cfg.D, n_q = (size_t)c->cfg.Hq * c->cfg.D;
-    size_t slices_kv = 1, slices_q = 1;
-    if (c->cfg.dtype == LCKV_BF16) {
-        slices_kv = (size_t)hidden / project_slice_channels((int)n_kv, hidden);
-        slices_q = (size_t)hidden / project_slice_channels((int)n_q, hidden);
-    }
-    size_t n = slices_kv * n_kv > slices_q * n_q ? slices_kv * n_kv : slices_q * n_q;
-    n *= (size_t)B * sizeof(float);
+    (void)hidden;
+    if (c->cfg.dtype == LCKV_BF16) return 0;
+    size_t n = ((size_t)c->cfg.Hq + 2 * (size_t)c->cfg.Hkv) * c->cfg.D * (size_t)B * sizeof(float);
     return (n + 255) / 256 * 256;
 }
 
 int lckv_pack_projection_weight(const lckv_cache *c, const void *w, void *w_packed, int32_t n_rows, int32_t hidden,
                                 void *hip_stream) {
     if (!valid(c) || !w || !w_packed) return LCKV_ERR_NULL;
-    if (n_rows < 16 || n_rows % 16 != 0 || hidden < 1 || (int64_t)n_rows * hidden > ((int64_t)1 << 40))
-        return LCKV_ERR_CONFIG;
+    if (n_rows < 16 || n_rows % c->cfg.D != 0 || hidden < 1 || (int64_t)n_rows * hidden > ((int64_t)1 << 40))
+        return LCKV_ERR_CONFIG;  // whole heads: the packed order keeps the rotary pairs of a head together
     if (c->cfg.dtype == LCKV_BF16 && hidden % 256 != 0) return LCKV_ERR_CONFIG;
     if (!aligned(w, 16) || !aligned(w_packed, 16)) return LCKV_ERR_ALIGN;
     if (w == w_packed) return LCKV_ERR_CONFIG;
     if (c->host_only) return LCKV_ERR_HIP;
-    hipError_t e = launch_pack_weight(w, w_packed, n_rows, hidden, c->cfg.dtype, (hipStream_t)hip_stream);
+    hipError_t e = launch_pack_weight(w, w_packed, n_rows, hidden, c->cfg.D, c->cfg.dtype, (hipStream_t)hip_stream);
     return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
 }
 
@@ -592,7 +587,7 @@ int lckv_project_qkv(lckv_cache *c, int32_t layer, const void *x, int32_t hidden
         return LCKV_ERR_ALIGN;
     size_t need = 0;
     lckv_project_workspace_bytes(c, B, hidden, &need);
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return LCKV_ERR_WORKSPACE;
+    if (need > 0 && (!workspace || !aligned(workspace, 256) || workspace_bytes < need)) return LCKV_ERR_WORKSPACE;
     if (c->host_only) return LCKV_ERR_HIP;
     float *acc = (float *)workspace;
     hipError_t e = launch_project(x, hidden, w_q, w_k, w_v, q_out, k_out, v_out, slot_view(c, slot >= 0 ? slot : 0),

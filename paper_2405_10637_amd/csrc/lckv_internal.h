@@ -95,8 +95,7 @@ hipError_t launch_bump(int32_t *seq_lens, int B, hipStream_t s);
 hipError_t launch_load_dense(const SlotView &v, const void *k, const void *vv, const int32_t *lens, int B, int T,
                              int D, int dtype,
                              int32_t *dev_err, hipStream_t s);
-int project_slice_channels(int n_total, int hidden);
-hipError_t launch_pack_weight(const void *src, void *dst, int N, int hidden, int dtype, hipStream_t s);
+hipError_t launch_pack_weight(const void *src, void *dst, int N, int hidden, int D, int dtype, hipStream_t s);
 hipError_t launch_project(const void *x, int hidden, const void *w_q, const void *w_k, const void *w_v, void *q_out,
                           void *k_out, void *v_out, const SlotView &slot, const int32_t *seq_lens, int B, int Hq, int Hkv, int D, int dtype,
                           float rope_base, float *acc, int32_t *dev_err, hipStream_t s);

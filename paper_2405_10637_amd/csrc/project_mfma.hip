@@ -6,29 +6,25 @@
 // head is paired with channel i + D/2, angle t_b * base^(-2i/D)), the queries written to q_out, the keys and
 // values stored straight into the slot at position t_b (the append of the decode step, fused).
 //
-// Two launches on the caller's stream:
-//   1. the matrix product, split over the hidden dimension into slices; every slice writes its partial sums
-//      [slice][B][N] in fp32 with plain stores (atomic adds from all XCDs onto one accumulator were measured:
-//      they resolve outside the per-XCD L2 and took 35x the time of the weight stream)
-//   2. finish: add the slices in a fixed order, rotate (angles formed in double), round once, scatter into
-//      q_out / the cache pages
+// bf16: ONE launch.  A workgroup of 4 waves owns one or two tiles of 16 output features over the WHOLE hidden
+// dimension and up to 64 sequences; the hidden dimension is cut among its four waves, which add their sums through
+// LDS at the end - no partial sums travel through memory, and the rotation, the rounding and the scatter into
+// q_out / the cache pages are the kernel's epilogue.  What makes the epilogue local is the order of the rows in the
+// packed weight image (made once, when the model is loaded, by the pack kernel below): a tile holds the rows of
+// 8 rotary pairs - channels i .. i+7 of a head and their partners i + D/2 .. - so a pair sits in two lanes of
+// one wave, 32 lanes apart, and is exchanged with one v_permlane32_swap.  Each wave streams its tiles' weights
+// straight into registers, a contiguous KiB per load, two chunks of the hidden dimension in flight; since no two
+// waves need the same hidden channels, the x operands go straight to registers too (from the L2: x is small).
+// Batches above 64 sequences are cut into parts that read the same weights at the same time on the same XCD,
+// which fetches them from HBM once.  fp32 (parity mode): a plain product and a finish kernel, two launches.
 // The product streams each weight once from HBM (what bounds it: 2 * N * hidden bytes against 4 * B flops per
-// weight) and is shaped for that.  A workgroup of 4 waves owns 128 output features x one slice of KSTEPS * 32
-// hidden channels x up to 128 sequences (in two rounds of 64, both x slices in LDS from the start).  Each wave owns two 16-feature tiles whose weights it loads straight
-// into registers, all of them issued before anything else (up to 128 KiB per workgroup in flight); meanwhile the
-// x slice is staged in LDS in matrix-operand order, shared by the waves; after one barrier the wave runs its
-// matrix instructions, each LDS read of an x operand feeding two of them.  Features on the rows of the tiles
-// (A operand = weights), sequences on the columns.  The weights are taken in a packed image (made once, when
-// the model is loaded, by the pack kernel below) whose tiles are in matrix-operand order, so that every load
-// instruction is a contiguous KiB, as for the cache pages: with row-major weights an instruction touched 64
-// bytes of 16 rows and the stream reached 2.0 TB/s at best.
+// weight).
 #include "bf16_mfma_common.h"
 
 namespace lckv {
 
 namespace {
 
-constexpr int kTileRows = 128;  // output features per workgroup (8 tiles of 16, two per wave)
 typedef __attribute__((address_space(3))) void *LdsPtr;
 
 struct ProjParams {
@@ -47,6 +43,8 @@ struct ProjParams {
     double log2_base;           // log2(rope base); rotate = 0: no rotation
     int32_t rotate;
     int32_t *dev_err;
+    int32_t n_bparts;           // bf16: parts of 64 (or fewer) sequences the batch is cut into
+    double rev_freq[64];        // bf16: base^(-2i/D) / (2 pi), i < D/2: turns per position of rotary pair i
 };
 
 // Row n of the stacked matrix -> pointer to that row's first element (rows never straddle: n_rows are multiples
@@ -66,8 +64,10 @@ __device__ __forceinline__ const E *stacked_row(const ProjParams &p, int n) {
 }
 
 // Tile (16 rows) t of the stacked matrix -> its packed bf16 image: [hidden/32 steps][64 lanes][8 channels], lane
-// (kb, r) of step s holding channels 32s + 8kb .. +7 of row r, i.e. the A operands of the tile in the order and
-// lane layout the matrix instruction takes them; a tile's image is contiguous (hidden * 32 bytes).
+// (kb, r) of step s holding channels 32s + 8kb .. +7 of the tile's row r, i.e. the A operands of the tile in the
+// order and lane layout the matrix instruction takes them; a tile's image is contiguous (hidden * 32 bytes).
+// Tile t of a matrix with heads of D channels holds, of head t / (D/16), the rows of 8 rotary pairs:
+// rows r < 8 are channels 8 (t % (D/16)) + r, rows r >= 8 their partners D/2 further on.
 __device__ __forceinline__ const char *stacked_tile(const ProjParams &p, int t) {
     int m = 0;
     if (t >= p.n_rows[0] / 16) {
@@ -81,129 +81,203 @@ __device__ __forceinline__ const char *stacked_tile(const ProjParams &p, int t) 
     return (const char *)p.w[m] + (int64_t)t * p.hidden * 32;
 }
 
-// Row-major [N][hidden] bf16 -> the packed image above.  One thread per 16-byte chunk.
-__global__ void pack_weight_bf16_kernel(const uint16_t *src, uint16_t *dst, int N, int hidden) {
+// Row-major [N][hidden] bf16 -> the packed image above.  One thread per 16-byte chunk of the image.
+__global__ void pack_weight_bf16_kernel(const uint16_t *src, uint16_t *dst, int N, int hidden, int D) {
     const int chunks_per_row = hidden / 8;
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)N * chunks_per_row) return;
-    const int n = (int)(i / chunks_per_row), ch = (int)(i % chunks_per_row);
-    const int t = n >> 4, r = n & 15, s = ch >> 2, kb = ch & 3;
-    const u32x4 v = *(const u32x4 *)(src + (int64_t)n * hidden + ch * 8);
-    *(u32x4 *)(dst + (((int64_t)t * (hidden / 32) + s) * 64 + kb * 16 + r) * 8) = v;
+    // image order: [tile][step][kb][r]
+    const int r = (int)(i & 15), kb = (int)((i >> 4) & 3);
+    const int64_t ts = i >> 6;
+    const int steps = hidden / 32, st = (int)(ts % steps), t = (int)(ts / steps);
+    const int tph = D / 16, head = t / tph, ti = t % tph;
+    const int row = head * D + 8 * ti + (r < 8 ? r : D / 2 + r - 8);
+    const u32x4 v = *(const u32x4 *)(src + (int64_t)row * hidden + st * 32 + kb * 8);
+    *(u32x4 *)(dst + i * 8) = v;
 }
 
-// Launch 1, bf16.  NB = 16-sequence blocks per pass (1, 2, 4 or 8), KSTEPS = matrix instructions (32 hidden
-// channels each) per slice.  grid (feature blocks, slices, passes of 16 * NB sequences).
-template <int NB, int KSTEPS, int ROUNDS>
-__global__ __launch_bounds__(256, (ROUNDS == 1 ? 2 : 1)) void project_bf16_kernel(ProjParams p) {
-    // The x slices in LDS, one buffer per round of 16 * NB sequences.  With 512-channel slices a sequence's slice
-    // is 1 KiB = one fully coalesced load instruction, so it is kept row-major, rows 1 KiB + 16 bytes apart: lane
-    // (kb, c) then reads its operand of step s at row c, byte 64s + 16kb, and the 16 lanes of a quarter wave fall
-    // on 16 different bank quadruples.  With 256-channel slices the image is in operand order (each instruction
-    // gathers 64 bytes of 16 sequences).
-    constexpr bool kRowMajor = KSTEPS == 16;
-    constexpr int kRowStride = KSTEPS * 64 + 16;
-    constexpr int kRoundBytes = kRowMajor ? NB * 16 * kRowStride : NB * KSTEPS * 1024;
-    constexpr int kDmaPerWave = kRowMajor ? 4 * NB : NB * KSTEPS / 4;  // load instructions per wave and round
-    __shared__ __attribute__((aligned(16))) char lds[ROUNDS * kRoundBytes];
+// The end of both bf16 kernels: the four waves' sums over their quarters of the hidden dimension are added in a
+// fixed order (the result does not depend on the launch), rotated, rounded once and stored.
+template <int TILES, int NB>
+__device__ __forceinline__ void project_reduce_and_store(const ProjParams &p, char *lds, int slot_bytes,
+                                                         const floatx4 (&acc)[TILES][NB], int tg, int b0, int wave,
+                                                         int lane) {
+    // wave w's sums live in its own slot of the LDS (the one its x chunks went through): [tile][block][lane]
+    auto red = [&](int w, int nt, int j) -> floatx4 & {
+        return *(floatx4 *)(lds + w * slot_bytes + ((nt * NB + j) * 64 + lane) * 16);
+    };
+    const int c = lane & 15, kb = lane >> 4;
+#pragma unroll
+    for (int nt = 0; nt < TILES; ++nt)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) red(wave, nt, j) = acc[nt][j];
+    __syncthreads();
+    for (int j = wave; j < NB; j += 4) {  // wave w finishes sequence block w
+        const int b = b0 + 16 * j + c;
+        int t_pos = 0;
+        if (b < p.B) t_pos = max(p.seq_lens[b], 0);
+#pragma unroll
+        for (int nt = 0; nt < TILES; ++nt) {
+            floatx4 y = red(0, nt, j);
+#pragma unroll
+            for (int w = 1; w < 4; ++w) y += red(w, nt, j);
+            // lane (kb, c) holds rows 4 kb .. + 3 of the tile for sequence b: kb < 2: channels i0 + 4 kb + e of the
+            // head, kb >= 2: their rotary partners.  a = the lower lane's value, b = the upper lane's, in both.
+            const int t = tg * TILES + nt, tph = p.D / 16;
+            const int hg = t / tph, i0 = 8 * (t % tph) + 4 * (kb & 1);
+            const bool is_v = hg >= p.Hq + p.Hkv, upper = kb >= 2;
+            float outv[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float lo = y[e], hi = y[e];
+                swap_halves32(lo, hi);
+                float cs = 1.f, sn = 0.f;
+                if (p.rotate && !is_v) {
+                    const double turns = (double)t_pos * p.rev_freq[i0 + e];
+                    const float fr = (float)(turns - floor(turns));
+                    sn = __builtin_amdgcn_sinf(fr);  // sine and cosine of 2 pi fr
+                    cs = __builtin_amdgcn_cosf(fr);
+                }
+                outv[e] = upper ? hi * cs + lo * sn : lo * cs - hi * sn;
+            }
+            if (b >= p.B) continue;
+            const int d0 = i0 + (upper ? p.D / 2 : 0);  // channels d0 .. d0 + 3 of head hg
+            const u32x2 pk = {pack_bf16(outv[0], outv[1]), pack_bf16(outv[2], outv[3])};
+            if (hg < p.Hq) {
+                *(u32x2 *)((uint16_t *)p.q_out + ((int64_t)b * p.Hq + hg) * p.D + d0) = pk;
+                continue;
+            }
+            const int g = is_v ? hg - p.Hq - p.Hkv : hg - p.Hq;
+            if (p.k_out) {  // handed back to the caller, who appends them after the layer's attention
+                *(u32x2 *)((uint16_t *)(is_v ? p.v_out : p.k_out) + ((int64_t)b * p.Hkv + g) * p.D + d0) = pk;
+                continue;
+            }
+            // into the slot at position t_b (the ring entry under the sink + window policy)
+            int entry = p.seq_lens[b];
+            if (entry >= 0) entry = entry_of_position(p.slot, entry);
+            if (entry < 0 || entry >= p.slot.capacity) {
+                if (d0 == 0) atomicOr(p.dev_err, LCKV_DEV_ERR_CAPACITY);
+                continue;
+            }
+            const int64_t pp = page_pair_index(p.slot, b, g, entry / kPage);
+            if (pp < 0) {
+                if (d0 == 0) atomicOr(p.dev_err, LCKV_DEV_ERR_BLOCK);
+                continue;
+            }
+            uint16_t *page = (uint16_t *)(p.slot.base + pp * (2 * (int64_t)p.slot.page_bytes) + (is_v ? p.slot.page_bytes : 0));
+            const int jpos = entry % kPage;
+            if (!is_v) {  // four channels of one octet: 8 contiguous bytes of the K page
+                *(u32x2 *)(page + k_elem_offset_bf16(jpos, d0)) = pk;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) page[v_elem_offset_bf16(jpos, d0 + e)] = (uint16_t)(pack_bf16(outv[e], 0.f) & 0xffffu);
+            }
+        }
+    }
+}
+
+// The bf16 projection.  TILES tiles of 16 features per workgroup, NB blocks of 16 sequences, KS steps of 32 hidden
+// channels per chunk.  grid: feature groups x batch parts, laid out so that the parts of one group follow each other
+// on one XCD.  Each wave streams the weights of its quarter of the hidden dimension into registers, a contiguous
+// KiB per load, two chunks in flight.  The x operands of a matrix instruction are 64 bytes of 16 different rows;
+// fetched like that (rows 2 * hidden bytes apart: one L2 channel at a time) they were measured three times slower
+// than the weight stream, so each wave fetches its x chunk as whole rows (KS * 64 contiguous bytes per row),
+// parks it in a wave-private piece of LDS with the 16-byte chunks of a row exchanged by the row number, and reads
+// the operands from there without bank conflicts.  One chunk of x in registers on its way, one in LDS being
+// used; no barrier before the final sum (nothing else is shared between waves).
+template <int TILES, int NB, int KS>
+__global__ __launch_bounds__(256) void project_staged_bf16_kernel(ProjParams p) {
+    constexpr int kRowBytes = KS * 64, kLpr = kRowBytes / 16;   // bytes / lanes per row of a chunk
+    constexpr int kRowsPerLoad = 64 / kLpr, kLoads = NB * 16 / kRowsPerLoad;
+    constexpr int kStage = NB * 16 * kRowBytes;
+    static_assert(kLoads >= 1 && kLpr <= 64, "a row of a chunk is at most one load instruction");
+    // the sums of the four waves are exchanged through the same LDS once the x chunks are done with
+    constexpr int kRed = TILES * NB * 64 * 16;
+    constexpr int kSlot = kStage > kRed ? kStage : kRed;
+    __shared__ __attribute__((aligned(16))) char xs[4][kSlot];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int r = lane & 15, kb = lane >> 4;
-    const int c0 = blockIdx.y * (KSTEPS * 32);
-    static_assert(NB * KSTEPS % 4 == 0, "tiles divide among the four waves");
-    static_assert(2 * KSTEPS + (ROUNDS - 1) * kDmaPerWave < 64, "the wait below counts this many loads");
+    const int c = lane & 15, kb = lane >> 4;
+    const int n_groups = p.n_total / (16 * TILES);
+    const int id = blockIdx.x;
+    const int tg = (id / (8 * p.n_bparts)) * 8 + id % 8, bp = (id / 8) % p.n_bparts;
+    if (tg >= n_groups) return;  // uniform
+    const int b0 = bp * (16 * NB);
+    const int ks_w = p.hidden / 128;          // steps of 32 channels per wave; a multiple of KS (checked by the host)
+    const int k_begin = wave * ks_w;
+    const char *wimg[TILES];
+#pragma unroll
+    for (int nt = 0; nt < TILES; ++nt) wimg[nt] = stacked_tile(p, tg * TILES + nt) + ((int64_t)k_begin * 64 + lane) * 16;
+    const char *xsrc[kLoads];  // load i: row i * kRowsPerLoad + lane / kLpr of the part, 16-byte chunk lane % kLpr
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+        const int row = i * kRowsPerLoad + lane / kLpr;
+        xsrc[i] = (const char *)p.x + ((int64_t)min(b0 + row, p.B - 1) * p.hidden + k_begin * 32) * 2 + (lane % kLpr) * 16;
+    }
+    char *stage = xs[wave];
 
-    // 1. The x slices of all rounds into LDS by direct global-to-LDS loads (issued as assembly: the compiler's
-    //    builtin would make every LDS read below wait on each of them separately).  Rows past the batch: the last
-    //    row, whose columns are never stored.
-    auto dma = [&](const uint16_t *src, const char *dst_lds) {  // lane l's 16 bytes land at dst_lds + 16 l
-        const uint32_t dst = (uint32_t)(uintptr_t)(LdsPtr)dst_lds;
-        uint32_t m0_saved;  // M0 carries the LDS address; whatever the compiler keeps there is put back
-        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
-                     "s_mov_b32 m0, %0"
-                     : "=&s"(m0_saved)
-                     : "s"(dst), "v"(src)
-                     : "memory");
+    floatx4 acc[TILES][NB];
+#pragma unroll
+    for (int nt = 0; nt < TILES; ++nt)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) acc[nt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 wa[TILES][KS], wb[TILES][KS], xraw[kLoads];
+    auto load_w = [&](u32x4 (&w)[TILES][KS], int ch) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int nt = 0; nt < TILES; ++nt)
+                w[nt][s] = __builtin_nontemporal_load((const u32x4 *)(wimg[nt] + (ch * KS + s) * 1024));
     };
+    auto load_x = [&](int ch) {
 #pragma unroll
-    for (int round = 0; round < ROUNDS; ++round) {
-        const int b0 = (blockIdx.z * ROUNDS + round) * (16 * NB);
-        const char *buf = lds + round * kRoundBytes;
-        if (kRowMajor) {
+        for (int i = 0; i < kLoads; ++i) xraw[i] = *(const u32x4 *)(xsrc[i] + ch * kRowBytes);
+    };
+    auto park_x = [&]() {
 #pragma unroll
-            for (int k = 0; k < kDmaPerWave; ++k) {  // one instruction per sequence
-                const int row = wave + 4 * k;
-                dma((const uint16_t *)p.x + (int64_t)min(b0 + row, p.B - 1) * p.hidden + c0 + lane * 8,
-                    buf + row * kRowStride);
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < kDmaPerWave; ++k) {  // one instruction per (sequence block j, step st) operand
-                const int tile = wave + 4 * k, j = tile / KSTEPS, st = tile % KSTEPS;
-                dma((const uint16_t *)p.x + (int64_t)min(b0 + 16 * j + r, p.B - 1) * p.hidden + c0 + st * 32 + kb * 8,
-                    buf + tile * 1024);
-            }
+        for (int i = 0; i < kLoads; ++i) {
+            const int row = i * kRowsPerLoad + lane / kLpr;
+            *(u32x4 *)(stage + row * kRowBytes + (((lane % kLpr) ^ (row & (kLpr - 1))) * 16)) = xraw[i];
         }
-    }
-
-    // 2. This wave's weights: two tiles x KSTEPS steps, from the packed image: every load instruction is one
-    //    contiguous, lane-ordered KiB and the KSTEPS loads of a tile are consecutive KiBs.  (A tile past the end
-    //    of the matrix reads the last tile instead, so that every wave has the same number of loads in flight.)
-    u32x4 wr[2][KSTEPS];
-    bool have[2];
-    const int last_tile = p.n_total / 16 - 1;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    auto use_chunk = [&](const u32x4 (&w)[TILES][KS]) {
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int t = blockIdx.x * (kTileRows / 16) + wave * 2 + nt;
-        have[nt] = t <= last_tile;  // wave-uniform
-        const char *img = stacked_tile(p, min(t, last_tile)) + ((int64_t)(c0 / 32) * 64 + lane) * 16;
-#pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) wr[nt][s] = __builtin_nontemporal_load((const u32x4 *)(img + s * 1024));
-    }
-
-    // 3. The first round's x has landed when at most the later loads are outstanding (loads complete in order):
-    //    the matrix instructions start on it while the weights are still streaming in - the compiler waits for
-    //    each weight register where it is first used.
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * KSTEPS + (ROUNDS - 1) * kDmaPerWave) : "memory");
-    float *part = p.acc + (int64_t)blockIdx.y * p.B * p.n_total;
-#pragma unroll
-    for (int round = 0; round < ROUNDS; ++round) {
-        const int b0 = (blockIdx.z * ROUNDS + round) * (16 * NB);
-        const char *buf = lds + round * kRoundBytes;
-        if (round > 0) {
-            if (b0 >= p.B) break;  // uniform
-            asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");  // every wave's share of this round's x
-        }
-        floatx4 acc[2][NB];
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-            for (int j = 0; j < NB; ++j) acc[nt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < KSTEPS; ++s)
+        for (int s = 0; s < KS; ++s)
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
-                const char *xp = kRowMajor ? buf + (16 * j + r) * kRowStride + (4 * s + kb) * 16
-                                           : buf + ((j * KSTEPS + s) * 64 + lane) * 16;
-                const bf16x8 xb = __builtin_bit_cast(bf16x8, *(const u32x4 *)xp);
+                const int row = 16 * j + c;
+                const u32x4 xb = *(const u32x4 *)(stage + row * kRowBytes + (((4 * s + kb) ^ (row & (kLpr - 1))) * 16));
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-                    acc[nt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wr[nt][s]), xb,
-                                                                         acc[nt][j], 0, 0, 0);
+                for (int nt = 0; nt < TILES; ++nt)
+                    acc[nt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[nt][s]),
+                                                                         __builtin_bit_cast(bf16x8, xb), acc[nt][j], 0, 0, 0);
             }
-
-        // lane (kb, c) holds features n0 + 4kb .. +3 of sequence b0 + 16j + c: 16 bytes of this slice's partial sums
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            if (!have[nt]) continue;
-            const int n0 = blockIdx.x * kTileRows + (wave * 2 + nt) * 16;
-#pragma unroll
-            for (int j = 0; j < NB; ++j) {
-                const int b = b0 + 16 * j + r;
-                if (b < p.B) *(floatx4 *)(part + (int64_t)b * p.n_total + n0 + 4 * kb) = acc[nt][j];
-            }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    const int n_chunks = ks_w / KS;
+    load_x(0);
+    load_w(wa, 0);
+    park_x();
+    for (int ch = 0; ch < n_chunks; ch += 2) {  // the weight registers take turns (no register copies)
+        if (ch + 1 < n_chunks) {
+            load_x(ch + 1);
+            load_w(wb, ch + 1);
         }
+        use_chunk(wa);
+        if (ch + 1 >= n_chunks) break;
+        park_x();
+        if (ch + 2 < n_chunks) {
+            load_x(ch + 2);
+            load_w(wa, ch + 2);
+        }
+        use_chunk(wb);
+        if (ch + 2 < n_chunks) park_x();
     }
+    project_reduce_and_store<TILES, NB>(p, &xs[0][0], kSlot, acc, tg, b0, wave, lane);
 }
 
 // Launch 1, fp32 (parity mode, not tuned): one thread per output, products accumulated in double.
@@ -299,21 +373,14 @@ __device__ __forceinline__ void finish_pair(const ProjParams &p, float2 cs, int 
 
 }  // namespace
 
-hipError_t launch_pack_weight(const void *src, void *dst, int N, int hidden, int dtype, hipStream_t s) {
+hipError_t launch_pack_weight(const void *src, void *dst, int N, int hidden, int D, int dtype, hipStream_t s) {
     if (dtype == LCKV_BF16) {
         const int64_t chunks = (int64_t)N * (hidden / 8);
         hipLaunchKernelGGL(pack_weight_bf16_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s,
-                           (const uint16_t *)src, (uint16_t *)dst, N, hidden);
+                           (const uint16_t *)src, (uint16_t *)dst, N, hidden, D);
         return hipGetLastError();
     }
     return hipMemcpyAsync(dst, src, (size_t)N * hidden * 4, hipMemcpyDeviceToDevice, s);  // fp32: row-major as is
-}
-
-// Hidden channels per slice for the bf16 product: 512 when that still gives every compute unit a workgroup, else
-// 256 (more, thinner slices).  Needs hidden % 256 == 0.
-int project_slice_channels(int n_total, int hidden) {
-    const int64_t blocks = (n_total + kTileRows - 1) / kTileRows;
-    return (hidden % 512 == 0 && blocks * (hidden / 512) >= 256) ? 512 : 256;
 }
 
 // x [B][hidden]; w_k / w_v null for a layer that produces no slot (then `slot` is not used).
@@ -346,35 +413,42 @@ hipError_t launch_project(const void *x, int hidden, const void *w_q, const void
 
     const int64_t n_acc = (int64_t)B * p.n_total;
     if (dtype == LCKV_BF16) {
-        // up to 64 sequences per round, up to two rounds per workgroup (the weights are read once per 128 sequences)
-        const int per_round = B > 32 ? 64 : B > 16 ? 32 : 16;
-        const int rounds = B > 64 ? 2 : 1;
-        const int ksteps = project_slice_channels(p.n_total, hidden) / 32;
-        p.n_slices = hidden / (ksteps * 32);
-        dim3 grid((p.n_total + kTileRows - 1) / kTileRows, p.n_slices, (B + per_round * rounds - 1) / (per_round * rounds));
-#define LCKV_PROJECT_LAUNCH(NB, ROUNDS)                                                   \
-    if (ksteps == 16)                                                                     \
-        hipLaunchKernelGGL((project_bf16_kernel<NB, 16, ROUNDS>), grid, dim3(256), 0, s, p); \
-    else                                                                                  \
-        hipLaunchKernelGGL((project_bf16_kernel<NB, 8, ROUNDS>), grid, dim3(256), 0, s, p)
-        if (rounds == 2) {
-            LCKV_PROJECT_LAUNCH(4, 2);
-        } else if (per_round == 64) {
-            LCKV_PROJECT_LAUNCH(4, 1);
-        } else if (per_round == 32) {
-            LCKV_PROJECT_LAUNCH(2, 1);
+        if (D / 2 > 64) return hipErrorInvalidValue;
+        for (int i = 0; i < D / 2; ++i)
+            p.rev_freq[i] = p.rotate ? pow((double)rope_base, -2.0 * i / D) / 6.283185307179586476925286766559 : 0.0;
+        // up to 64 sequences per workgroup; batches up to 64 take one tile per workgroup (more workgroups, each
+        // reading all of x), small ones longer chunks (more weight bytes in flight per wave)
+        const int per_part = B > 32 ? 64 : B > 16 ? 32 : 16;
+        const int tiles = B > 64 ? 2 : 1;  // measured: B = 64: 0.54 ms per step with one tile, 0.62 with two; B = 128: 0.89 / 0.69
+        p.n_bparts = (B + per_part - 1) / per_part;
+        const int n_groups = p.n_total / (16 * tiles);
+        dim3 grid((unsigned)((n_groups + 7) / 8 * 8 * p.n_bparts));
+        // hidden channels per chunk: as many steps as divide a wave's quarter (hidden / 128 steps, an even number)
+        // and as the registers of this batch shape hold
+        const int ks_w = hidden / 128;
+        const int ks_max = per_part == 64 ? 4 : per_part == 32 ? 8 : 16;
+        int ks = 2;
+        while (ks * 2 <= ks_max && ks_w % (ks * 2) == 0) ks *= 2;
+#define LCKV_PROJECT_LAUNCH(T, NB, KS) \
+    hipLaunchKernelGGL((project_staged_bf16_kernel<T, NB, KS>), grid, dim3(256), 0, s, p)
+        if (per_part == 64) {
+            if (tiles == 2) {
+                if (ks == 4) LCKV_PROJECT_LAUNCH(2, 4, 4); else LCKV_PROJECT_LAUNCH(2, 4, 2);
+            } else {
+                if (ks == 4) LCKV_PROJECT_LAUNCH(1, 4, 4); else LCKV_PROJECT_LAUNCH(1, 4, 2);
+            }
+        } else if (per_part == 32) {
+            if (ks == 8) LCKV_PROJECT_LAUNCH(1, 2, 8); else if (ks == 4) LCKV_PROJECT_LAUNCH(1, 2, 4); else LCKV_PROJECT_LAUNCH(1, 2, 2);
         } else {
-            LCKV_PROJECT_LAUNCH(1, 1);
+            if (ks == 16) LCKV_PROJECT_LAUNCH(1, 1, 16); else if (ks == 8) LCKV_PROJECT_LAUNCH(1, 1, 8);
+            else if (ks == 4) LCKV_PROJECT_LAUNCH(1, 1, 4); else LCKV_PROJECT_LAUNCH(1, 1, 2);
         }
 #undef LCKV_PROJECT_LAUNCH
-    } else {
-        p.n_slices = 1;
-        hipLaunchKernelGGL(project_f32_kernel, dim3((unsigned)((n_acc + 255) / 256)), dim3(256), 0, s, p);
+        return hipGetLastError();
     }
-    if (dtype == LCKV_BF16)
-        hipLaunchKernelGGL(project_finish_kernel<uint16_t>, dim3((unsigned)((n_acc / 2 + 255) / 256)), dim3(256), 0, s, p);
-    else
-        hipLaunchKernelGGL(project_finish_kernel<uint32_t>, dim3((unsigned)((n_acc / 2 + 255) / 256)), dim3(256), 0, s, p);
+    p.n_slices = 1;
+    hipLaunchKernelGGL(project_f32_kernel, dim3((unsigned)((n_acc + 255) / 256)), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(project_finish_kernel<uint32_t>, dim3((unsigned)((n_acc / 2 + 255) / 256)), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
