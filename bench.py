@@ -312,6 +312,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="capture one lckv_step in a HIP graph (length bound = last timed step) and time replays")
+    ap.add_argument("--one-launch", action="store_true",
+                    help="the step through lckv_step_one_launch: one resident kernel, a device-wide barrier between "
+                         "layers (for small slots, where a layer's pass lasts about as long as a launch)")
     ap.add_argument("--chain", action="store_true",
                     help="feed layer l's output into layer l+1's query (q[l+1] = q_seed[l+1] + out[l]) so the "
                          "layer-to-layer dependency of the model is physically real; per-layer entry points")
@@ -370,6 +373,10 @@ def main():
             sys.exit("--chain and --graph are separate modes")
         q_seed, q = q, torch.empty_like(q)
         one_step = lambda: sess.step_chained(q_seed, k_new, v_new, q, out)
+    elif args.one_launch:
+        if args.graph:
+            sys.exit("--one-launch and --graph are separate modes (a cooperative launch is not captured)")
+        one_step = lambda: sess.step_one_launch(q, k_new, v_new, out)
     else:
         one_step = lambda: sess.step(q, k_new, v_new, out)
 
@@ -437,6 +444,8 @@ def main():
     ev_first = first_timed + (K if args.graph else 0)   # the steps whose launches carried the events
     ev_bytes = sum(sess.kv_bytes_per_step(ev_first + i) for i in range(K)) + qo_bytes
     alg_bytes_per_launch = ev_bytes / float(K * wl.L)
+    if args.one_launch:   # one kernel per step: its duration is the step's (no per-layer events inside a launch)
+        n_launch, kern_ms, alg_bytes_per_launch = K, ms_per_step * K, ev_bytes / float(K)
     avg_kernel_ms = kern_ms / max(n_launch, 1)
     achieved = alg_bytes_per_launch / (avg_kernel_ms * 1e-3) / 1e9
     step_gbps = (kv_bytes + qo_bytes) / K / (ms_per_step * 1e-3) / 1e9
@@ -452,7 +461,8 @@ def main():
         "metric": METRIC.get(args.workload, "decode attention tokens/s (all layers, %s)" % wl.name),
         "value": wl.B / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.dtype, "data": "synthetic", "launch": "hip-graph replay" if args.graph else ("eager, chained layers" if args.chain else "eager"),
+        "dtype": wl.dtype, "data": "synthetic", "launch": "hip-graph replay" if args.graph else ("eager, chained layers" if args.chain else
+                                                         "one launch, device-wide barriers" if args.one_launch else "eager"),
         "config": {"workload": "%s: L=%d w=%d Hq=%d Hkv=%d D=%d B=%d T=%s%s" % (
             wl.name, wl.L, wl.w, wl.Hq, wl.Hkv, wl.D, wl.B,
             wl.T if wl.T_min is None else "U[%d,%d]" % (wl.T_min, wl.T), " paged16" if wl.paged else ""),
@@ -460,7 +470,8 @@ def main():
         "step_effective_GBps": step_gbps, "step_pct_of_hbm_peak": 100.0 * step_gbps / HBM_PEAK_GBPS,
         "read_probe_GBps": probe_gbps,
         "cache_fill_import_GBps": [round(x, 1) for x in sess.import_GBps],   # lckv_cache_load_dense, read + write
-        "roofline": {"bound": "hbm", "kernel": "attn_%s_kernel" % ("bf16" if wl.dtype == "bf16" else "f32"),
+        "roofline": {"bound": "hbm", "kernel": "step_bf16_kernel" if args.one_launch else
+                     "attn_%s_kernel" % ("bf16" if wl.dtype == "bf16" else "f32"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": traffic, "launches": n_launch, "avg_launch_ms": avg_kernel_ms,
                      "alg_bytes_per_launch": alg_bytes_per_launch},

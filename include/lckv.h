@@ -68,6 +68,8 @@ extern "C" {
 /* Sticky device-side error bits reported by lckv_last_device_error. */
 #define LCKV_DEV_ERR_CAPACITY 1     /* a sequence length reached the capacity; the access was skipped/clamped */
 #define LCKV_DEV_ERR_BLOCK 2        /* a block-table entry was outside [0, num_blocks); the page was skipped */
+#define LCKV_DEV_ERR_BARRIER 4      /* lckv_step_one_launch: a wait at the device-wide barrier between two layers ran
+                                       into its time bound; the workgroups left the kernel, the step is incomplete */
 
 /* Size of the library's own scratch array (device memory inside the loaded library, one copy per GPU), used by
  * lckv_step_static_scratch. */
@@ -217,6 +219,21 @@ int lckv_pack_projection_weight(const lckv_cache *cache, const void *w, void *w_
 int lckv_step(lckv_cache *cache, const void *q_all, const void *k_new_all, const void *v_new_all, void *out_all,
               int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint, void *workspace, size_t workspace_bytes,
               void *hip_stream);
+
+/* The same step in ONE kernel launch (bf16 caches; LCKV_ERR_CONFIG otherwise), for slots so small that a layer's pass
+ * over its slot lasts about as long as a kernel launch (the TinyLlama-shaped workload: 22 layers of 128 MiB).  A
+ * grid that is resident all at once walks the layers in index order; a device-wide barrier ends every layer's
+ * attention, so layer l+1 still starts only when layer l's results are complete; the merge of layer l's split
+ * partials and the shared slot's append run right after that barrier.  Same units of work and same arithmetic
+ * as lckv_step: the results are the same bit for bit.  workspace: at least lckv_step_one_launch_workspace_bytes
+ * (two sets of split partials, used in turn).  The barrier's waits are bounded (a few seconds by default,
+ * lckv_set_barrier_wait_ms in lckv_tools.h): if one expires, LCKV_DEV_ERR_BARRIER is raised and every workgroup
+ * leaves the kernel.  A cooperative launch: do not capture it in a HIP graph, and enqueue at most one such step
+ * per cache at a time (all launches of a cache share two barrier counters, used in turn). */
+int lckv_step_one_launch(lckv_cache *cache, const void *q_all, const void *k_new_all, const void *v_new_all,
+                         void *out_all, int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint, void *workspace,
+                         size_t workspace_bytes, void *hip_stream);
+int lckv_step_one_launch_workspace_bytes(const lckv_cache *cache, int32_t B, int32_t max_len_hint, size_t *bytes);
 
 /* lckv_step for callers that cannot allocate device memory and so have no workspace to pass: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace,

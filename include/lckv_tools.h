@@ -28,6 +28,11 @@ int lckv_set_load_policy(lckv_cache *cache, int32_t policy);
  * Host only. */
 int lckv_set_prefill_tile(lckv_cache *cache, int32_t query_blocks_per_wave);
 
+/* Bound on a wait at the device-wide barrier of lckv_step_one_launch, in milliseconds (default 2000; 0 makes
+ * the first workgroup to arrive give up at once - the tests use that to walk the error path: every workgroup
+ * leaves the kernel, LCKV_DEV_ERR_BARRIER is raised).  Host only. */
+int lckv_set_barrier_wait_ms(lckv_cache *cache, double ms);
+
 /* Kernel timing for benchmarks: while enabled, every attention kernel launch is bracketed by HIP events on
  * its stream (do not enable during graph capture).  lckv_profile_read SYNCHRONISES, returns the number of
  * timed launches and their summed duration since the last read, and resets both. */

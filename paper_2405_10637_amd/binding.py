@@ -20,7 +20,7 @@ LCKV_ERR_LENGTH, LCKV_ERR_WORKSPACE, LCKV_ERR_ALIGN, LCKV_ERR_BLOCK_TABLE, LCKV_
 LCKV_ERR_MASK, LCKV_ERR_STORAGE, LCKV_ERR_RANGE = -11, -12, -13
 LCKV_BF16, LCKV_F32 = 0, 1
 LCKV_PAIR_TOP_OF_CONDENSED, LCKV_PAIR_LAST_LAYER = 0, 1
-LCKV_DEV_ERR_CAPACITY, LCKV_DEV_ERR_BLOCK = 1, 2
+LCKV_DEV_ERR_CAPACITY, LCKV_DEV_ERR_BLOCK, LCKV_DEV_ERR_BARRIER = 1, 2, 4
 LCKV_LOAD_AUTO, LCKV_LOAD_TEMPORAL, LCKV_LOAD_NONTEMPORAL = 0, 1, 2
 LCKV_STATIC_SCRATCH_BYTES = 32 << 20
 
@@ -28,7 +28,7 @@ EXPORTS = [
     "lckv_cache_bytes", "lckv_plan_max_batch", "lckv_cache_alloc", "lckv_cache_free", "lckv_cache_set_block_table", "lckv_n_slots",
     "lckv_kv_slot", "lckv_slot_producer", "lckv_append_kv", "lckv_decode_attention", "lckv_prefill_attention",
     "lckv_set_prefill_tile", "lckv_project_qkv", "lckv_project_workspace_bytes", "lckv_pack_projection_weight", "lckv_step",
-    "lckv_step_static_scratch",
+    "lckv_step_static_scratch", "lckv_step_one_launch", "lckv_step_one_launch_workspace_bytes", "lckv_set_barrier_wait_ms",
     "lckv_workspace_bytes", "lckv_set_split_tokens", "lckv_set_load_policy", "lckv_cache_load_dense", "lckv_cache_read",
     "lckv_last_device_error", "lckv_profile_enable", "lckv_profile_read", "lckv_profile_launch_ms",
     "lckv_hbm_read_probe", "lckv_strerror",
@@ -81,6 +81,9 @@ def lib():
         L.lckv_pack_projection_weight.argtypes = [vp, vp, vp, i32, i32, vp]
         L.lckv_step.argtypes =[vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
         L.lckv_step_static_scratch.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp]
+        L.lckv_step_one_launch.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
+        L.lckv_step_one_launch_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
+        L.lckv_set_barrier_wait_ms.argtypes = [vp, ctypes.c_double]
         L.lckv_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
         L.lckv_set_split_tokens.argtypes = [vp, i32]
         L.lckv_set_load_policy.argtypes = [vp, i32]
@@ -213,6 +216,26 @@ def lckv_step(cache: int, q_all, k_new_all, v_new_all, out_all, dev_seq_lens, B:
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lckv_step(cache, _ptr(q_all), _ptr(k_new_all), _ptr(v_new_all), _ptr(out_all), _ptr(dev_seq_lens), B,
                            max_len_hint, _ptr(workspace), workspace_bytes, _stream(stream)), "lckv_step")
+
+
+def lckv_step_one_launch(cache: int, q_all, k_new_all, v_new_all, out_all, dev_seq_lens, B: int, max_len_hint: int,
+                         workspace=None, workspace_bytes: Optional[int] = None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lckv_step_one_launch(cache, _ptr(q_all), _ptr(k_new_all), _ptr(v_new_all), _ptr(out_all),
+                                      _ptr(dev_seq_lens), B, max_len_hint, _ptr(workspace), workspace_bytes,
+                                      _stream(stream)), "lckv_step_one_launch")
+
+
+def lckv_step_one_launch_workspace_bytes(cache: int, B: int, max_len_hint: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().lckv_step_one_launch_workspace_bytes(cache, B, max_len_hint, ctypes.byref(out)),
+           "lckv_step_one_launch_workspace_bytes")
+    return out.value
+
+
+def lckv_set_barrier_wait_ms(cache: int, ms: float):
+    _check(lib().lckv_set_barrier_wait_ms(cache, float(ms)), "lckv_set_barrier_wait_ms")
 
 
 def lckv_step_static_scratch(cache: int, q_all, k_new_all, v_new_all, out_all, dev_seq_lens, B: int, max_len_hint: int,

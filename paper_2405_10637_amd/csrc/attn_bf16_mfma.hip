@@ -141,16 +141,16 @@ __device__ __forceinline__ void consume_tile(Tile<D, NP> &t, const bf16x8 (&qb)[
     }
 }
 
-// W waves per workgroup, NP pages (of 16 keys) per wave and tile.
+// One (split, kv head, sequence) unit of a layer's attention, by one workgroup of W waves; NP pages (of 16 keys)
+// per wave and tile.  `launch_unit` is the unit's place in launch order (sequence-major, kv head minor): the order
+// is scattered over the units by a multiplier coprime to their number.  Workgroups that run at the same time then
+// read streams that lie far apart and at unrelated distances, instead of neighbours at one fixed distance whose
+// addresses can fall on the same HBM channels; together with the rotated page walk below this makes the
+// bandwidth independent of the cache capacity chosen (measured: 6.6-7.0 TB/s depending on the capacity without
+// it).  Uses LDS; a workgroup that takes several units in a row synchronises between them.
 template <int D, int NP, int W, bool PAGED, bool NT>
-__global__ __launch_bounds__(W * 64) void attn_bf16_kernel(AttnParams p) {
-    // Which (sequence, kv head) this workgroup takes: the launch order is scattered over the units by a
-    // multiplier coprime to their number.  Workgroups that run at the same time then read streams that lie far
-    // apart and at unrelated distances, instead of neighbours at one fixed distance whose addresses can fall on
-    // the same HBM channels; together with the rotated page walk below this makes the bandwidth independent of
-    // the cache capacity chosen (measured: 6.6-7.0 TB/s depending on the capacity without it).
-    const int split = blockIdx.x;
-    const int unit = (int)(((int64_t)(blockIdx.z * p.Hkv + blockIdx.y) * p.unit_mul) % ((int64_t)p.B * p.Hkv));
+__device__ __forceinline__ void attn_bf16_unit(const AttnParams &p, int split, int launch_unit) {
+    const int unit = (int)(((int64_t)launch_unit * p.unit_mul) % ((int64_t)p.B * p.Hkv));
     const int g = unit % p.Hkv, b = unit / p.Hkv;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: page numbers stay uniform
@@ -282,6 +282,11 @@ __global__ __launch_bounds__(W * 64) void attn_bf16_kernel(AttnParams p) {
         p.part_ml[((int64_t)split * p.B + b) * p.Hq + h] = float2{M, L};
 }
 
+template <int D, int NP, int W, bool PAGED, bool NT>
+__global__ __launch_bounds__(W * 64) void attn_bf16_kernel(AttnParams p) {
+    attn_bf16_unit<D, NP, W, PAGED, NT>(p, blockIdx.x, blockIdx.z * p.Hkv + blockIdx.y);
+}
+
 template <int D, int NP, int W>
 static hipError_t launch_variant(const AttnParams &p, hipStream_t s) {
     dim3 grid(p.n_splits, p.Hkv, p.B), block(W * 64);
@@ -303,6 +308,144 @@ hipError_t launch_attn_bf16(const AttnParams &p, int D, hipStream_t s) {
     // One page per wave and tile: measured fastest on MI355X for the Llama-7B shape (three waves per SIMD fit in
     // the register file; two- and four-page tiles were 1-2 % slower).
     return D == 128 ? launch_variant<128, 1, 4>(p, s) : launch_variant<64, 1, 4>(p, s);
+}
+
+// The whole decode step in ONE launch, for slots so small that a layer's pass lasts about as long as a kernel
+// launch (TinyLlama shape: 128 MiB, 17 us at the HBM peak): a grid that is resident all at once walks the layers in
+// index order; a device-wide barrier ends every layer's attention, so layer l + 1 starts only when layer l's
+// partial results are complete (in the model its query depends on layer l's output, Section 2.1).  After the
+// barrier the workgroups first merge layer l's split partials (two sets of partials, taken in turn, so that the
+// next layer's can be written meanwhile) and store the shared slot's new K/V if layer l produces them, then go on
+// with layer l + 1.  The units of a layer - (split, kv head, sequence), the same as the per-layer launch's, so the
+// results are the same bit for bit - are dealt round-robin to the workgroups.
+// The barrier is an arrival counter in device memory: one thread per workgroup publishes the workgroup's stores
+// (release fence at device scope), counts itself in and polls until all have arrived, then an acquire fence.  The
+// wait is bounded: when the bound expires the thread raises LCKV_DEV_ERR_BARRIER and its workgroup leaves the
+// kernel, and so does every other workgroup when its own bound expires - nothing waits for ever.
+template <int D, bool PAGED, bool NT>
+__global__ __launch_bounds__(256) void step_bf16_kernel(StepParams sp) {
+    __shared__ int sm_failed;
+    const int tid = threadIdx.x;
+    const int64_t kv_elems = (int64_t)sp.a.B * sp.a.Hkv * D;
+    const int64_t layer_bytes = (int64_t)sp.a.B * sp.a.Hq * D * 2;
+    uint32_t arrivals = 0;
+    // `acquire`: also drop what this compute unit and its L2 may hold of other workgroups' data from BEFORE the
+    // barrier.  Needed only where plain loads after the barrier read addresses that were read earlier in this
+    // launch and written since; an invalidation of the L2 by every workgroup at every barrier was measured to cost
+    // more than the attention itself.  The merge reads the partials with device-scope loads instead, which need none.
+    auto barrier = [&](bool acquire) -> bool {
+        ++arrivals;
+        __syncthreads();  // every wave of this workgroup has finished the phase
+        if (tid == 0) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // the workgroup's stores, out of this XCD's L2
+            // arrivals are counted in kBarrierGroups groups and the groups in a top counter: read-modify-writes on
+            // one address are served one after the other, and several hundred of them per barrier took longer
+            // than a layer's attention
+            const uint32_t n_groups = min((uint32_t)kBarrierGroups, gridDim.x);
+            const uint32_t gi = blockIdx.x % n_groups;
+            const uint32_t group_size = (gridDim.x - gi + n_groups - 1) / n_groups;
+            if (atomicAdd(sp.barrier + 1 + gi, 1u) + 1u == arrivals * group_size) atomicAdd(sp.barrier, 1u);
+            const uint32_t target = arrivals * n_groups;
+            const long long t0 = wall_clock64();
+            int failed = 0;
+            while (__hip_atomic_load(sp.barrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+                if (wall_clock64() - t0 > sp.wait_ticks) {
+                    atomicOr(sp.a.dev_err, LCKV_DEV_ERR_BARRIER);
+                    failed = 1;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(32);  // about 1 us between polls
+            }
+            if (acquire) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            sm_failed = failed;
+        }
+        __syncthreads();
+        return sm_failed == 0;
+    };
+    auto slot_view_of = [&](int slot) {
+        SlotView sv = sp.a.slot;
+        sv.base = sp.storage + (int64_t)slot * sp.slot_bytes;
+        return sv;
+    };
+    auto append_slot = [&](int slot) {
+        const SlotView sv = slot_view_of(slot);
+        const uint16_t *k = (const uint16_t *)sp.k_new_all + slot * kv_elems, *v = (const uint16_t *)sp.v_new_all + slot * kv_elems;
+        for (int64_t i = (int64_t)blockIdx.x * 256 + tid; i < kv_elems; i += (int64_t)gridDim.x * 256)
+            append_element<uint16_t>(sv, k, v, sp.a.seq_lens, D, sp.a.dev_err, i);
+    };
+    if (blockIdx.x == 0 && tid <= kBarrierGroups) sp.barrier_next[tid] = 0u;
+
+    // warmup layers' new K/V into their private slots (read by nobody else): all at the start, one barrier
+    bool any = false;
+    for (int l = 0; l < sp.L; ++l)
+        if (sp.layer_table[4 * l + 3] == kAppendAtStart) {
+            append_slot(sp.layer_table[4 * l + 2]);
+            any = true;
+        }
+    if (any && !barrier(false)) return;  // nothing of these slots has been read in this launch yet
+
+    for (int l = 0; l < sp.L; ++l) {
+        const int slot = sp.layer_table[4 * l], vis = sp.layer_table[4 * l + 1];
+        const int produced = sp.layer_table[4 * l + 2], when = sp.layer_table[4 * l + 3];
+        if (when == kAppendBeforeOwnAttention) {  // a slot other layers read too: only now, and a barrier of its own
+            append_slot(produced);
+            if (!barrier(true)) return;  // the layers below have read this slot's last page in this launch
+        }
+        AttnParams p = sp.a;
+        p.slot = slot_view_of(slot);
+        p.q = sp.q_all + l * layer_bytes;
+        p.out = sp.out_all + l * layer_bytes;
+        p.self_visible = vis;
+        p.max_n = sp.max_n[vis];
+        p.split_tokens = sp.split_tokens[vis];
+        p.n_splits = sp.n_splits[vis];
+        p.part_o = sp.part_o[l & 1];
+        p.part_ml = sp.part_ml[l & 1];
+        const int n_units = p.n_splits * sp.a.Hkv * sp.a.B;
+        for (int u = blockIdx.x; u < n_units; u += gridDim.x) {
+            attn_bf16_unit<D, 1, 4, PAGED, NT>(p, u % p.n_splits, u / p.n_splits);
+            __syncthreads();  // the unit's LDS is free again
+        }
+        if (!barrier(false)) return;
+        if (p.n_splits > 1) {
+            const int64_t rows = (int64_t)sp.a.B * sp.a.Hq;
+            for (int64_t i = (int64_t)blockIdx.x * 256 + tid; i < rows * D; i += (int64_t)gridDim.x * 256)
+                combine_element<uint16_t, true>(p.part_o, p.part_ml, (uint16_t *)p.out, rows, D, p.n_splits, i);
+        }
+        if (when == kAppendAfterOwnAttention) append_slot(produced);
+    }
+    // the lengths are read by the appends: one more barrier if the last layer appended after its attention
+    if (sp.layer_table[4 * (sp.L - 1) + 3] == kAppendAfterOwnAttention && !barrier(false)) return;
+    if (blockIdx.x == 0)
+        for (int i = tid; i < sp.a.B; i += 256) sp.seq_lens_rw[i] += 1;
+}
+
+template <int D, bool PAGED, bool NT>
+static hipError_t launch_step_variant(const StepParams &sp, int max_units, hipStream_t s) {
+    static int resident = 0;  // workgroups of this kernel the device holds at once (asked once)
+    if (resident == 0) {
+        int per_cu = 0, dev = 0;
+        hipDeviceProp_t prop;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, step_bf16_kernel<D, PAGED, NT>, 256, 0) != hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess || per_cu < 1)
+            return hipErrorInvalidValue;
+        resident = per_cu * prop.multiProcessorCount;
+    }
+    int grid = max_units < resident ? max_units : resident;
+    if (grid < 1) grid = 1;
+    StepParams copy = sp;
+    void *args[] = {&copy};
+    return hipLaunchCooperativeKernel((const void *)step_bf16_kernel<D, PAGED, NT>, dim3(grid), dim3(256), args, 0, s);
+}
+
+hipError_t launch_step_bf16(const StepParams &sp, int D, int max_units, hipStream_t s) {
+    // one load policy for the whole launch (the condensed layers'; the policy never changes a result)
+    const bool paged = sp.a.slot.table != nullptr, nt = sp.nontemporal[0] != 0;
+#define LCKV_STEP_LAUNCH(DD)                                                                             \
+    (paged ? (nt ? launch_step_variant<DD, true, true>(sp, max_units, s) : launch_step_variant<DD, true, false>(sp, max_units, s)) \
+           : (nt ? launch_step_variant<DD, false, true>(sp, max_units, s) : launch_step_variant<DD, false, false>(sp, max_units, s)))
+    return D == 128 ? LCKV_STEP_LAUNCH(128) : LCKV_STEP_LAUNCH(64);
+#undef LCKV_STEP_LAUNCH
 }
 
 // Measurement aid: stream `bytes` of device memory through the same access pattern the attention kernel uses

@@ -7,50 +7,13 @@ namespace lckv {
 
 namespace {
 
-constexpr float kNegInf = -__builtin_huge_valf();
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(2))) float floatx2;
-
-template <typename E>
-__device__ __forceinline__ int k_off(int j, int d, int D);
-template <>
-__device__ __forceinline__ int k_off<uint16_t>(int j, int d, int) { return k_elem_offset_bf16(j, d); }
-template <>
-__device__ __forceinline__ int k_off<uint32_t>(int j, int d, int D) { return kv_elem_offset_f32(j, d, D); }
-template <typename E>
-__device__ __forceinline__ int v_off(int j, int d, int D);
-template <>
-__device__ __forceinline__ int v_off<uint16_t>(int j, int d, int) { return v_elem_offset_bf16(j, d); }
-template <>
-__device__ __forceinline__ int v_off<uint32_t>(int j, int d, int D) { return kv_elem_offset_f32(j, d, D); }
-
 // K[slot][b][t_b] = k_new[b], V likewise (Section 2.1: the K/V of a producing layer are cached for later
 // tokens).  One thread per (b, kv head, channel); E is the element's bit pattern type.
 template <typename E>
 __global__ void append_kernel(SlotView sv, const E *k_new, const E *v_new, const int32_t *seq_lens, int B, int D,
                               int32_t *dev_err) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t total = (int64_t)B * sv.Hkv * D;
-    if (i >= total) return;
-    int d = (int)(i % D);
-    int g = (int)((i / D) % sv.Hkv);
-    int b = (int)(i / ((int64_t)D * sv.Hkv));
-    int t = seq_lens[b];
-    if (t >= 0) t = entry_of_position(sv, t);  // identity, or the ring entry under the sink + window policy
-    if (t < 0 || t >= sv.capacity) {
-        if (d == 0) atomicOr(dev_err, LCKV_DEV_ERR_CAPACITY);
-        return;
-    }
-    int64_t idx = page_pair_index(sv, b, g, t / kPage);
-    if (idx < 0) {
-        if (d == 0) atomicOr(dev_err, LCKV_DEV_ERR_BLOCK);
-        return;
-    }
-    E *kpage = (E *)(sv.base + idx * (2 * (int64_t)sv.page_bytes));
-    E *vpage = (E *)((char *)kpage + sv.page_bytes);
-    int j = t % kPage;
-    kpage[k_off<E>(j, d, D)] = k_new[i];
-    vpage[v_off<E>(j, d, D)] = v_new[i];
+    if (i < (int64_t)B * sv.Hkv * D) append_element<E>(sv, k_new, v_new, seq_lens, D, dev_err, i);
 }
 
 // Dense [B][T][Hkv][D] -> cache, positions [0, min(T, lens[b])), any element type (used for fp32 caches, the
@@ -206,33 +169,11 @@ __global__ void bump_kernel(int32_t *seq_lens, int B) {
     if (i < B) seq_lens[i] += 1;
 }
 
-__device__ __forceinline__ void store_out(float *o, float v) { *o = v; }
-__device__ __forceinline__ void store_out(uint16_t *o, float v) {
-    floatx2 f = {v, 0.f};
-    bf16x2 h = __builtin_convertvector(f, bf16x2);  // round to nearest even
-    *o = (uint16_t)(__builtin_bit_cast(uint32_t, h) & 0xffffu);
-}
-
-// Merge of split partials: with (m_i, l_i, o_i) the running maximum (log2 units), denominator and
-// unnormalised output of split i,  out = sum_i 2^(m_i - M) o_i / sum_i 2^(m_i - M) l_i,  M = max_i m_i.
-// Splits without a visible key carry m_i = -inf and are skipped; no visible key at all gives zero.
+// Merge of split partials, one thread per output element.
 template <typename O>
 __global__ void combine_kernel(const float *part_o, const float2 *part_ml, O *out, int64_t rows, int D, int S) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= rows * D) return;
-    int64_t row = i / D;
-    int d = (int)(i % D);
-    float M = kNegInf;
-    for (int s = 0; s < S; ++s) M = fmaxf(M, part_ml[(int64_t)s * rows + row].x);
-    float num = 0.f, den = 0.f;
-    for (int s = 0; s < S; ++s) {
-        float2 ml = part_ml[(int64_t)s * rows + row];
-        if (ml.x == kNegInf) continue;
-        float f = exp2f(ml.x - M);
-        den += f * ml.y;
-        num += f * part_o[((int64_t)s * rows + row) * D + d];
-    }
-    store_out(out + i, den > 0.f ? num / den : 0.f);
+    if (i < rows * D) combine_element<O>(part_o, part_ml, out, rows, D, S, i);
 }
 
 inline unsigned blocks_for(int64_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }

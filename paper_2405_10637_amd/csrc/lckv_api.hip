@@ -257,6 +257,36 @@ int check_call(const lckv_cache *c, int B, int max_len_hint, int extra) {
     return LCKV_OK;
 }
 
+// Per layer, for the one-launch step: the slot it reads, whether it sees itself, the slot it produces and when that
+// slot's new K/V may be stored.  A warmup layer's private slot (read by nobody else): at the start of the step.  A
+// slot that other layers read too: by a producer that sees itself, right before its own attention (the layers
+// below have read the slot by then); by a condensed producer, after its own attention (no condensed layer sees the
+// token being decoded, and under the sink + window policy the entry it replaces is still read until then).
+int upload_layer_table(lckv_cache *c) {
+    const int L = c->cfg.L;
+    std::vector<int32_t> t(4 * (size_t)L);
+    for (int l = 0; l < L; ++l) {
+        int produced = -1;
+        for (int s = 0; s < c->n_slots; ++s)
+            if (c->producer[s] == l) produced = s;
+        int when = kAppendNone;
+        if (produced >= 0) {
+            bool shared = false;
+            for (int k = 0; k < L; ++k)
+                if (k != l && c->kv_slot[k] == produced) shared = true;
+            when = !c->self_visible[l] ? kAppendAfterOwnAttention : shared ? kAppendBeforeOwnAttention : kAppendAtStart;
+        }
+        t[4 * l] = c->kv_slot[l];
+        t[4 * l + 1] = c->self_visible[l];
+        t[4 * l + 2] = produced;
+        t[4 * l + 3] = when;
+    }
+    if (hipMalloc((void **)&c->dev_layer_table, t.size() * sizeof(int32_t)) != hipSuccess) return LCKV_ERR_HIP;
+    if (hipMemcpy(c->dev_layer_table, t.data(), t.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess)
+        return LCKV_ERR_HIP;
+    return LCKV_OK;
+}
+
 // The slot whose K/V `layer` produces, or -1.
 int produced_slot(const lckv_cache *c, int layer) {
     for (int s = 0; s < c->n_slots; ++s)
@@ -324,6 +354,9 @@ int lckv_cache_alloc(const lckv_config *cfg, void *kv_storage, size_t kv_bytes, 
     c->profiling = false;
     c->ev_used = 0;
     c->dev_err = nullptr;
+    c->dev_layer_table = nullptr;
+    c->step_launches = 0;
+    c->barrier_wait_ms = 2000.0;
     c->scratch = nullptr;
     // A host without a GPU still gets a handle: the pairing table, the planners and every argument check work
     // on it, and each call that would enqueue work returns LCKV_ERR_HIP after its checks.
@@ -332,8 +365,9 @@ int lckv_cache_alloc(const lckv_config *cfg, void *kv_storage, size_t kv_bytes, 
     if (c->host_only) {
         (void)hipGetLastError();
     } else if (hipMalloc((void **)&c->dev_err, 256) != hipSuccess || hipMemset(c->dev_err, 0, 256) != hipSuccess ||
-               static_scratch_of_current_device(&c->scratch) != LCKV_OK) {
+               static_scratch_of_current_device(&c->scratch) != LCKV_OK || upload_layer_table(c) != LCKV_OK) {
         if (c->dev_err) (void)hipFree(c->dev_err);
+        if (c->dev_layer_table) (void)hipFree(c->dev_layer_table);
         c->magic = 0;
         delete c;
         return LCKV_ERR_HIP;
@@ -346,6 +380,7 @@ int lckv_cache_free(lckv_cache *c) {
     if (!valid(c)) return LCKV_ERR_NULL;
     for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
     if (c->dev_err) (void)hipFree(c->dev_err);
+    if (c->dev_layer_table) (void)hipFree(c->dev_layer_table);
     c->magic = 0;
     delete c;
     return LCKV_OK;
@@ -515,6 +550,87 @@ int lckv_step(lckv_cache *c, const void *q_all, const void *k_new_all, const voi
                      workspace_bytes, false, hip_stream);
 }
 
+int lckv_step_one_launch_workspace_bytes(const lckv_cache *c, int32_t B, int32_t max_len_hint, size_t *bytes) {
+    int rc = lckv_workspace_bytes(c, B, max_len_hint, bytes);
+    if (rc == LCKV_OK) *bytes *= 2;  // two sets of split partials, taken in turn by layer parity
+    return rc;
+}
+
+int lckv_step_one_launch(lckv_cache *c, const void *q_all, const void *k_new_all, const void *v_new_all,
+                         void *out_all, int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint, void *workspace,
+                         size_t workspace_bytes, void *hip_stream) {
+    if (!valid(c) || !q_all || !k_new_all || !v_new_all || !out_all || !dev_seq_lens) return LCKV_ERR_NULL;
+    if (c->cfg.dtype != LCKV_BF16) return LCKV_ERR_CONFIG;
+    int rc = check_call(c, B, max_len_hint, 1);  // the new token must fit
+    if (rc != LCKV_OK) return rc;
+    if (!aligned(q_all, 16) || !aligned(out_all, 16) || !aligned(k_new_all, 16) || !aligned(v_new_all, 16) ||
+        !aligned(dev_seq_lens, 4))
+        return LCKV_ERR_ALIGN;
+    size_t one = 0;
+    rc = lckv_workspace_bytes(c, B, max_len_hint, &one);
+    if (rc != LCKV_OK) return rc;
+    if (one > 0 && (!workspace || !aligned(workspace, 256) || workspace_bytes < 2 * one)) return LCKV_ERR_WORKSPACE;
+    if (c->host_only) return LCKV_ERR_HIP;
+
+    const lckv_config &cfg = c->cfg;
+    StepParams sp{};
+    sp.a.slot = slot_view(c, 0);
+    sp.a.seq_lens = dev_seq_lens;
+    sp.a.dev_err = c->dev_err;
+    sp.a.B = B;
+    sp.a.Hq = cfg.Hq;
+    sp.a.Hkv = cfg.Hkv;
+    sp.a.G = cfg.Hq / cfg.Hkv;
+    sp.a.scale_log2e = c->scale * 1.4426950408889634f;
+    sp.a.unit_mul = 1;
+    for (int prime : {2731, 1571, 7919, 104729})  // as in the per-layer launch
+        if (((int64_t)B * cfg.Hkv) % prime != 0) {
+            sp.a.unit_mul = prime;
+            break;
+        }
+    int max_units = 1;
+    for (int vis = 0; vis < 2; ++vis) {
+        const int max_n = visible_bound(c, max_len_hint, vis);
+        const SplitPlan plan = plan_splits(c, B, max_n);
+        sp.max_n[vis] = max_n;
+        sp.split_tokens[vis] = plan.tokens;
+        sp.n_splits[vis] = plan.n_splits;
+        const double pass_bytes = (double)B * max_n * 2.0 * cfg.Hkv * cfg.D * elem_bytes(cfg.dtype);
+        sp.nontemporal[vis] = c->load_policy == LCKV_LOAD_NONTEMPORAL ||
+                              (c->load_policy == LCKV_LOAD_AUTO && pass_bytes > kLastLevelCacheBytes);
+        const int64_t units = (int64_t)plan.n_splits * cfg.Hkv * B;
+        if (units > max_units) max_units = (int)(units > (1 << 30) ? (1 << 30) : units);
+    }
+    sp.a.clamp_is_policy = cfg.window_tokens > 0 && sp.max_n[0] == kept_capacity(c);
+    {   // two sets of partials; in each, the (m, l) pairs lie past the partial outputs of the plan with more splits
+        const int ns = sp.n_splits[0] > sp.n_splits[1] ? sp.n_splits[0] : sp.n_splits[1];
+        const size_t rows = (size_t)ns * B * cfg.Hq;
+        const size_t o_bytes = (rows * cfg.D * sizeof(float) + 255) / 256 * 256;
+        for (int k = 0; k < 2; ++k) {
+            sp.part_o[k] = one ? (float *)((char *)workspace + k * one) : nullptr;
+            sp.part_ml[k] = one ? (float2 *)((char *)workspace + k * one + o_bytes) : nullptr;
+        }
+    }
+    sp.q_all = (const char *)q_all;
+    sp.out_all = (char *)out_all;
+    sp.k_new_all = (const char *)k_new_all;
+    sp.v_new_all = (const char *)v_new_all;
+    sp.storage = c->storage;
+    sp.slot_bytes = (int64_t)c->slot_bytes;
+    sp.layer_table = c->dev_layer_table;
+    sp.L = cfg.L;
+    sp.seq_lens_rw = dev_seq_lens;
+    // two sets of 1 + kBarrierGroups counters in the handle's device block (words 8.. and 32.., zero at first)
+    static_assert(8 + 1 + kBarrierGroups <= 32 && 32 + 1 + kBarrierGroups <= 64, "the device block has 64 words");
+    uint32_t *counters = (uint32_t *)c->dev_err;
+    sp.barrier = counters + ((c->step_launches & 1u) ? 32 : 8);
+    sp.barrier_next = counters + ((c->step_launches & 1u) ? 8 : 32);
+    sp.wait_ticks = (int64_t)(c->barrier_wait_ms * 1e5);  // the wall clock ticks at 100 MHz
+    c->step_launches += 1;
+    hipError_t e = launch_step_bf16(sp, cfg.D, max_units, (hipStream_t)hip_stream);
+    return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
+}
+
 int lckv_step_static_scratch(lckv_cache *c, const void *q_all, const void *k_new_all, const void *v_new_all,
                              void *out_all, int32_t *dev_seq_lens, int32_t B, int32_t max_len_hint,
                              void *hip_stream) {
@@ -600,6 +716,13 @@ int lckv_set_split_tokens(lckv_cache *c, int32_t tokens) {
     if (!valid(c)) return LCKV_ERR_NULL;
     if (tokens < 0 || tokens % kPage != 0) return LCKV_ERR_CONFIG;
     c->forced_split_tokens = tokens;
+    return LCKV_OK;
+}
+
+int lckv_set_barrier_wait_ms(lckv_cache *c, double ms) {
+    if (!valid(c)) return LCKV_ERR_NULL;
+    if (!(ms >= 0.0) || ms > 60000.0) return LCKV_ERR_CONFIG;
+    c->barrier_wait_ms = ms;
     return LCKV_OK;
 }
 

@@ -46,7 +46,7 @@ class DecodeSession:
         self.steps_left = room
         self.import_GBps = []     # read + write rate of each lckv_cache_load_dense call made by fill()
         ws = max(lk.lckv_workspace_bytes(self.h, wl.B, self.max_len + i) for i in range(room + 1))
-        self.workspace = torch.empty(max(ws, 256), dtype=torch.uint8, device=DEV)
+        self.workspace = torch.empty(max(2 * ws, 256), dtype=torch.uint8, device=DEV)   # 2x: the one-launch step's
 
     def close(self):
         if self.h:
@@ -98,6 +98,13 @@ class DecodeSession:
     def step(self, q, k_new, v_new, out):
         assert self.steps_left > 0, "cache capacity used up"
         lk.lckv_step(self.h, q, k_new, v_new, out, self.lens, self.wl.B, self.max_len, self.workspace)
+        self.max_len += 1
+        self.steps_left -= 1
+
+    def step_one_launch(self, q, k_new, v_new, out):
+        """The same step through lckv_step_one_launch (bf16 caches)."""
+        assert self.steps_left > 0, "cache capacity used up"
+        lk.lckv_step_one_launch(self.h, q, k_new, v_new, out, self.lens, self.wl.B, self.max_len, self.workspace)
         self.max_len += 1
         self.steps_left -= 1
 
