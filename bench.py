@@ -24,6 +24,32 @@ METRIC = {
 }
 
 
+def kernel_source_hash(files=("attn_bf16_mfma.hip", "bf16_mfma_common.h", "lckv_internal.h")):
+    """sha256 over the sources the attention kernel is built from.  A counter summary under profiles/ carries the
+    hash of the sources it was measured on; bench.py quotes its traffic figure only while the hash still matches."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in files:
+        h.update(open(os.path.join(ROOT, "paper_2405_10637_amd", "csrc", f), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload):
+    """(bytes per launch, note) from profiles/attn_kernel_<workload>_hbm_traffic.txt, or (None, why not)."""
+    tpath = os.path.join(ROOT, "profiles", "attn_kernel_%s_hbm_traffic.txt" % workload)
+    if not os.path.exists(tpath):
+        return None, "no counter summary for this workload under profiles/"
+    traffic = stamp = None
+    for line in open(tpath):
+        if line.startswith("traffic_bytes_per_launch:"):
+            traffic = float(line.split(":")[1])
+        if line.startswith("kernel_source_sha256:"):
+            stamp = line.split(":")[1].strip()
+    if stamp != kernel_source_hash():
+        return None, "the counter summary under profiles/ was measured on other kernel sources (hash differs)"
+    return traffic, "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (same kernel sources, by hash)"
+
+
 def key_visits_per_step(lens, self_visible, Hq, step_index=0):
     """(query head, key) pairs one decode step evaluates: every layer l, sequence b and query head attends to
     lens[b] + step_index keys, plus the token itself in a warmup layer (Section 2.1).  The CPU oracle's sample is
@@ -102,8 +128,10 @@ def residency_sweep(steps, warmup):
     rows = []
     for B in (16, 32, 48, 64, 96, 128, 192, 256, 512):
         wl = synth.C2.with_(B=B, name="C2-shape-B%d" % B)
-        with DecodeSession(wl, room=2 * (steps + warmup) + 2) as sess:
-            sess.fill(())
+        with DecodeSession(wl, room=2 * (steps + warmup) + 4) as sess:
+            warm = [l for l in range(wl.L) if sess.kv_slot[l][1]]
+            units = [(1, 0, 0), (wl.L // 2, B - 1, wl.Hq - 1), (warm[-1], B // 2, 5)]   # condensed, condensed, warmup
+            kv = sess.fill(units)
             q, k_new, v_new = synth.step_inputs(wl, sess.n_slots, device="cuda")
             out = torch.empty_like(q)
             per_key = 2 * wl.Hkv * wl.D * wl.elem_bytes
@@ -111,6 +139,17 @@ def residency_sweep(steps, warmup):
             row = {"B": B, "shared_slot_MiB": B * wl.T * per_key / 2 ** 20}
             for name, policy in (("plain", lk.LCKV_LOAD_TEMPORAL), ("nontemporal", lk.LCKV_LOAD_NONTEMPORAL)):
                 lk.lckv_set_load_policy(sess.h, policy)
+                if name == "plain":     # the first step of each policy is checked against the oracle on sampled units
+                    lens_before = sess.lens.clone()
+                else:
+                    sess.lens.copy_(lens_before)      # the same step again with the other load policy
+                    sess.max_len, sess.steps_left = int(sess.lens0.max()), sess.steps_left + steps + warmup + 1
+                sess.step(q, k_new, v_new, out)
+                torch.cuda.synchronize()
+                base = cpu_baseline(sess, units, kv, q, k_new, v_new, out, target_cpu_s=0.0)
+                if base["max_abs_err_vs_gpu"] > 2e-2 or base["max_abs_err_vs_gpu"] > 1e-2 * max(base["max_abs_expected"], 1e-3):
+                    sys.exit("residency sweep, B=%d, %s loads: GPU output disagrees with the oracle: %r" % (B, name, base))
+                row.setdefault("max_abs_err_vs_oracle", {})[name] = base["max_abs_err_vs_gpu"]
                 for _ in range(warmup):
                     sess.step(q, k_new, v_new, out)
                 torch.cuda.synchronize()
@@ -450,12 +489,7 @@ def main():
     achieved = alg_bytes_per_launch / (avg_kernel_ms * 1e-3) / 1e9
     step_gbps = (kv_bytes + qo_bytes) / K / (ms_per_step * 1e-3) / 1e9
 
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "attn_kernel_%s_hbm_traffic.txt" % args.workload)
-    if os.path.exists(tpath):   # bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-        for line in open(tpath):
-            if line.startswith("traffic_bytes_per_launch:"):
-                traffic = float(line.split(":")[1])
+    traffic, traffic_note = measured_traffic(args.workload)
 
     rec = {
         "metric": METRIC.get(args.workload, "decode attention tokens/s (all layers, %s)" % wl.name),
@@ -473,7 +507,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "step_bf16_kernel" if args.one_launch else
                      "attn_%s_kernel" % ("bf16" if wl.dtype == "bf16" else "f32"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": traffic, "launches": n_launch, "avg_launch_ms": avg_kernel_ms,
+                     "traffic": traffic, "traffic_source": traffic_note, "launches": n_launch, "avg_launch_ms": avg_kernel_ms,
                      "alg_bytes_per_launch": alg_bytes_per_launch},
         "cpu_baseline": base,
     }
