@@ -180,7 +180,11 @@ __global__ __launch_bounds__(256, (D * QT <= 128 ? LCKV_PF_OCC : 1)) void prefil
     //   positions 4 hf .. 4 hf + 3 at quad hf and 8 + 4 hf .. at quad hf + 2 of the V page's
     //   [channel pair][quad][16 channels][2][4 positions] order - 8 bytes each, 512 bytes apart.
     const int k_lane = (c >> 4) * kPair + (hf * kPage + (c & 15)) * 16;
-    const int v_lane = kPair / 2 + ((hf * 16 + (c & 15)) * 2 + (c >> 4)) * 8;
+    //   Which channel a lane's row of the tile stands for is free (the output rows are sorted out at the end): row c
+    //   is channel 32 dt + 16 (c % 2) + c / 2, which makes the 8-byte pieces of lanes 0..31 (and of 32..63)
+    //   contiguous in LDS - with row c = channel c, neighbouring lanes' pieces lie 16 bytes apart and the two-address
+    //   reads were measured at half the rate (152 against 285 bytes per ns and compute unit).
+    const int v_lane = kPair / 2 + (hf * 32 + c) * 8;
 
     // One pair of pages (32 keys) against the wave's QT tiles of 32 queries.  DIAG = false: every key of the pair
     // is visible to every row of the wave - no masks.  DIAG = true: the diagonal or the end of the prompt crosses
@@ -349,7 +353,9 @@ __global__ __launch_bounds__(256, (D * QT <= 128 ? LCKV_PF_OCC : 1)) void prefil
     }
     if (!active) return;
 
-    // O^T accumulator register e of channel tile dt: channel 32 dt + 8 (e / 4) + 4 hf + e % 4 of query column c.
+    // O^T accumulator register e of channel tile dt: row i = 8 (e / 4) + 4 hf + e % 4 of the tile, i.e. channel
+    // 32 dt + 16 (i % 2) + i / 2, of query column c: registers 4 q .. 4 q + 3 are channels a, 16 + a, a + 1, 17 + a
+    // with a = 4 q + 2 hf.
     // The rounded rows are turned around in LDS (a piece of the tile buffers that nobody reads any more: not the
     // last tile's, which a slower wave may still be consuming) so that they leave as whole 2 D-byte rows, several
     // rows per store instruction, instead of 8-byte pieces of 32 different rows.
@@ -370,10 +376,13 @@ __global__ __launch_bounds__(256, (D * QT <= 128 ? LCKV_PF_OCC : 1)) void prefil
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
                 const floatx16 &a16 = acc[x][dt];
-                u32x2 pk = {pack_bf16(a16[4 * q4] * inv, a16[4 * q4 + 1] * inv),
-                            pack_bf16(a16[4 * q4 + 2] * inv, a16[4 * q4 + 3] * inv)};
-                const int chunk = 4 * dt + q4;  // channels 8 chunk .. + 7; this lane's half: 4 hf .. + 3
-                *(u32x2 *)(stage + c * kRowBytes + ((chunk ^ (c & (kCpr - 1))) * 16) + 8 * hf) = pk;
+                const uint32_t lo = pack_bf16(a16[4 * q4] * inv, a16[4 * q4 + 2] * inv);      // channels a, a + 1
+                const uint32_t hi = pack_bf16(a16[4 * q4 + 1] * inv, a16[4 * q4 + 3] * inv);  // channels 16 + a, 17 + a
+                const int a = 4 * q4 + 2 * hf;                                               // within the tile of 32
+                const int chunk_lo = 4 * dt + (a >> 3), chunk_hi = chunk_lo + 2;             // 16-byte chunks of 8 channels
+                char *row = stage + c * kRowBytes;
+                *(uint32_t *)(row + ((chunk_lo ^ (c & (kCpr - 1))) * 16) + (a & 7) * 2) = lo;
+                *(uint32_t *)(row + ((chunk_hi ^ (c & (kCpr - 1))) * 16) + (a & 7) * 2) = hi;
             }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
