@@ -343,6 +343,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--split-tokens", type=int, default=0)
+    ap.add_argument("--waves", type=int, default=0, help="waves per decode-attention workgroup (0 auto, 4, 8, 16)")
     ap.add_argument("--load-policy", type=int, default=0, help="0 auto, 1 plain loads, 2 nontemporal loads")
     ap.add_argument("--sample", type=int, default=768, help="units the CPU oracle is timed and checked on")
     ap.add_argument("--capacity", type=int, default=0,
@@ -398,7 +399,7 @@ def main():
         if args.capacity < wl.T + room:
             sys.exit("--capacity must be at least %d for this run" % (wl.T + room))
         room = args.capacity - wl.T
-    sess = DecodeSession(wl, room=room, split_tokens=args.split_tokens)
+    sess = DecodeSession(wl, room=room, split_tokens=args.split_tokens, waves=args.waves)
     lk.lckv_set_load_policy(sess.h, args.load_policy)
     units = []
     if not args.no_cpu_baseline:

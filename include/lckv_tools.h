@@ -16,6 +16,13 @@ extern "C" {
  * of a sequence's keys never depends on other sequences' lengths.  Host only; meant for tests and tuning. */
 int lckv_set_split_tokens(lckv_cache *cache, int32_t tokens);
 
+/* Force the width of the bf16 decode-attention workgroups: 4, 8 or 16 waves (16 only at D = 64; a larger request
+ * is cut to what D allows), 0 = the planner's choice.  By default a plan of two splits becomes one workgroup of 8
+ * waves and, at D = 64, a plan of three or four splits one of 16 waves: its waves are merged through LDS and no
+ * split partials go through memory.  With a forced width the number of splits stays what it would be at width 4
+ * (or what lckv_set_split_tokens asks for).  fp32 caches ignore it.  Host only. */
+int lckv_set_workgroup_waves(lckv_cache *cache, int32_t waves);
+
 /* How the attention kernels read K/V: AUTO uses the nontemporal hint when one layer's pass over its slot is
  * larger than the 256 MB last-level cache (nothing of it would survive until the next layer's pass), plain loads
  * otherwise (a small shared slot is re-read by every condensed layer and may stay cached).  Host only. */

@@ -29,7 +29,7 @@ EXPORTS = [
     "lckv_kv_slot", "lckv_slot_producer", "lckv_append_kv", "lckv_decode_attention", "lckv_prefill_attention",
     "lckv_set_prefill_tile", "lckv_project_qkv", "lckv_project_workspace_bytes", "lckv_pack_projection_weight", "lckv_step",
     "lckv_step_static_scratch", "lckv_step_one_launch", "lckv_step_one_launch_workspace_bytes", "lckv_set_barrier_wait_ms",
-    "lckv_workspace_bytes", "lckv_set_split_tokens", "lckv_set_load_policy", "lckv_cache_load_dense", "lckv_cache_read",
+    "lckv_workspace_bytes", "lckv_set_split_tokens", "lckv_set_workgroup_waves", "lckv_set_load_policy", "lckv_cache_load_dense", "lckv_cache_read",
     "lckv_last_device_error", "lckv_profile_enable", "lckv_profile_read", "lckv_profile_launch_ms",
     "lckv_hbm_read_probe", "lckv_strerror",
 ]
@@ -86,6 +86,7 @@ def lib():
         L.lckv_set_barrier_wait_ms.argtypes = [vp, ctypes.c_double]
         L.lckv_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(sz)]
         L.lckv_set_split_tokens.argtypes = [vp, i32]
+        L.lckv_set_workgroup_waves.argtypes = [vp, i32]
         L.lckv_set_load_policy.argtypes = [vp, i32]
         L.lckv_cache_load_dense.argtypes = [vp, i32, vp, vp, vp, i32, i32, vp]
         L.lckv_cache_read.argtypes = [vp, i32, i32, i32, i32, vp, vp]
@@ -275,6 +276,10 @@ def lckv_workspace_bytes(cache: int, B: int, max_len_hint: int) -> int:
 
 def lckv_set_split_tokens(cache: int, tokens: int):
     _check(lib().lckv_set_split_tokens(cache, tokens), "lckv_set_split_tokens")
+
+
+def lckv_set_workgroup_waves(cache: int, waves: int):
+    _check(lib().lckv_set_workgroup_waves(cache, waves), "lckv_set_workgroup_waves")
 
 
 def lckv_set_load_policy(cache: int, policy: int):

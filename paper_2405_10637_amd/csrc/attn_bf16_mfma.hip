@@ -158,6 +158,22 @@ __device__ __forceinline__ void attn_bf16_unit(const AttnParams &p, int split, i
     const int G = p.G;
     const int h = g * G + c;                  // query head of this lane's column (valid if c < G)
 
+    const int64_t row = (int64_t)b * p.Hq + h;
+
+    // Q^T operands: lane (kb, c) holds channels ks*32 + 8kb .. +8 of query head h; columns >= G are zero.  Asked
+    // for before the sequence's length is looked at, so that the two round trips to memory overlap (with small
+    // slots a workgroup's whole stream lasts only some twenty microseconds).
+    bf16x8 qb[D / 32];
+    {
+        const char *qp = (const char *)p.q + (row * D + kb * 8) * 2;
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ++ks) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (c < G) v = *(const u32x4 *)(qp + ks * 64);
+            qb[ks] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+
     int n = p.seq_lens[b] + p.self_visible;
     if (n > p.max_n) {
         n = p.max_n;
@@ -166,7 +182,6 @@ __device__ __forceinline__ void attn_bf16_unit(const AttnParams &p, int split, i
     if (n < 0) n = 0;
     const int k_begin = split * p.split_tokens;
     const int k_end = min(n, k_begin + p.split_tokens);
-    const int64_t row = (int64_t)b * p.Hq + h;
 
     if (k_begin >= k_end) {  // nothing visible in this split
         if (p.n_splits == 1) {
@@ -177,18 +192,6 @@ __device__ __forceinline__ void attn_bf16_unit(const AttnParams &p, int split, i
             p.part_ml[((int64_t)split * p.B + b) * p.Hq + g * G + tid] = float2{kNegInf, 0.f};
         }
         return;
-    }
-
-    // Q^T operands: lane (kb, c) holds channels ks*32 + 8kb .. +8 of query head h; columns >= G are zero.
-    bf16x8 qb[D / 32];
-    {
-        const char *qp = (const char *)p.q + (row * D + kb * 8) * 2;
-#pragma unroll
-        for (int ks = 0; ks < D / 32; ++ks) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (c < G) v = *(const u32x4 *)(qp + ks * 64);
-            qb[ks] = __builtin_bit_cast(bf16x8, v);
-        }
     }
 
     floatx4 acc[D / 16];
@@ -239,7 +242,7 @@ __device__ __forceinline__ void attn_bf16_unit(const AttnParams &p, int split, i
     // denominators were kept per lane: add the four key quads of each column
     l = column_sum4(l);
 
-    // merge the four waves: (m, l, O) per query column through LDS
+    // merge the W waves: (m, l, O) per query column through LDS
     __shared__ float sm_m[W][16];
     __shared__ float sm_l[W][16];
     __shared__ floatx4 sm_acc[W][D / 16][64];
@@ -261,7 +264,7 @@ __device__ __forceinline__ void attn_bf16_unit(const AttnParams &p, int split, i
         f[w] = (mw == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
         L += f[w] * sm_l[w][c];
     }
-    // wave w finishes channel tiles w, w + 4, ...
+    // wave w finishes channel tiles w, w + W, ...
     for (int j = wave; j < D / 16; j += W) {
         floatx4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -306,8 +309,12 @@ static hipError_t launch_variant(const AttnParams &p, hipStream_t s) {
 
 hipError_t launch_attn_bf16(const AttnParams &p, int D, hipStream_t s) {
     // One page per wave and tile: measured fastest on MI355X for the Llama-7B shape (three waves per SIMD fit in
-    // the register file; two- and four-page tiles were 1-2 % slower).
-    return D == 128 ? launch_variant<128, 1, 4>(p, s) : launch_variant<64, 1, 4>(p, s);
+    // the register file; two- and four-page tiles were 1-2 % slower).  Workgroups of 8 or 16 waves stand in for
+    // two or up to four splits (the host's plan): the merge of the waves through LDS is then the whole merge.
+    if (p.waves != 4 && p.waves != 8 && !(p.waves == 16 && D == 64)) return hipErrorInvalidValue;
+    if (D == 128) return p.waves == 8 ? launch_variant<128, 1, 8>(p, s) : launch_variant<128, 1, 4>(p, s);
+    if (p.waves == 16) return launch_variant<64, 1, 16>(p, s);
+    return p.waves == 8 ? launch_variant<64, 1, 8>(p, s) : launch_variant<64, 1, 4>(p, s);
 }
 
 // The whole decode step in ONE launch, for slots so small that a layer's pass lasts about as long as a kernel

@@ -150,12 +150,14 @@ SlotView slot_view(const lckv_cache *c, int slot) {
 
 struct SplitPlan {
     int32_t tokens, n_splits;
+    int32_t waves;  // per workgroup: 4, or 8 / 16 where one wide workgroup replaces 2 / 3-4 splits (bf16 only)
 };
 
 // Keys per split: fixed by B, Hkv and the length bound only, never by an individual sequence's length, so a
 // sequence's result does not depend on which other sequences share the batch.
-SplitPlan plan_splits(const lckv_cache *c, int B, int max_n) {
+SplitPlan plan_splits(const lckv_cache *c, int B, int max_n, bool allow_wide = true) {
     SplitPlan p;
+    p.waves = 4;
     if (max_n < 1) max_n = 1;
     if (c->forced_split_tokens > 0) {
         p.tokens = c->forced_split_tokens;
@@ -172,6 +174,25 @@ SplitPlan plan_splits(const lckv_cache *c, int B, int max_n) {
         p.tokens = (int32_t)((t + 63) / 64 * 64);
     }
     p.n_splits = (max_n + p.tokens - 1) / p.tokens;
+    if (allow_wide && c->cfg.dtype == LCKV_BF16) {
+        // A few splits only: the waves of those splits go into ONE workgroup instead, which merges them through
+        // LDS - the same number of waves stream the same keys, but no partial results go through memory and no
+        // merge kernel follows (for small slots that kernel and its launch are a fifth of a layer's time).  The
+        // merge buffer in LDS bounds the width: 16 waves at D = 64, 8 at D = 128.
+        const int widest = c->cfg.D == 64 ? 16 : 8;
+        int waves = 4;
+        if (c->forced_waves > 0)
+            waves = c->forced_waves <= widest ? c->forced_waves : widest;
+        else if (c->forced_split_tokens == 0 && p.n_splits == 2)
+            waves = 8;
+        else if (c->forced_split_tokens == 0 && (p.n_splits == 3 || p.n_splits == 4) && widest == 16)
+            waves = 16;
+        if (waves > 4 && c->forced_waves == 0) {
+            p.tokens = (max_n + 63) / 64 * 64;
+            p.n_splits = 1;
+        }
+        p.waves = waves;
+    }
     return p;
 }
 
@@ -214,6 +235,7 @@ int attention_impl(lckv_cache *c, int layer, const void *q, void *out, const int
     p.clamp_is_policy = cfg.window_tokens > 0 && max_n == kept_capacity(c);
     p.split_tokens = sp.tokens;
     p.n_splits = sp.n_splits;
+    p.waves = sp.waves;
     p.scale_log2e = c->scale * 1.4426950408889634f;
     // K/V of one layer's pass: B * n * 2 * Hkv * D * elem bytes.  Past the size of the last-level cache nothing
     // of it survives until the next layer reads the slot again, and the nontemporal hint makes the stream faster.
@@ -348,6 +370,7 @@ int lckv_cache_alloc(const lckv_config *cfg, void *kv_storage, size_t kv_bytes, 
     c->max_blocks = 0;
     c->capacity = cfg->page_size ? 0 : g.pages_per_seq * kPage;
     c->forced_split_tokens = 0;
+    c->forced_waves = 0;
     c->load_policy = LCKV_LOAD_AUTO;
     c->prefill_query_blocks = 0;  // 0: chosen per head dimension at launch
     c->scale = cfg->scale > 0.f ? cfg->scale : 1.0f / sqrtf((float)cfg->D);
@@ -550,8 +573,19 @@ int lckv_step(lckv_cache *c, const void *q_all, const void *k_new_all, const voi
                      workspace_bytes, false, hip_stream);
 }
 
+// Split partials of the larger of the two plans (with and without the new token visible).
+int partials_bytes(const lckv_cache *c, int32_t B, int32_t max_len_hint, bool allow_wide, size_t *bytes) {
+    if (!valid(c) || !bytes) return LCKV_ERR_NULL;
+    if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
+    if (max_len_hint < 0) return LCKV_ERR_LENGTH;
+    size_t a = workspace_need(c, B, plan_splits(c, B, visible_bound(c, max_len_hint, 0), allow_wide).n_splits);
+    size_t b = workspace_need(c, B, plan_splits(c, B, visible_bound(c, max_len_hint, 1), allow_wide).n_splits);
+    *bytes = a > b ? a : b;
+    return LCKV_OK;
+}
+
 int lckv_step_one_launch_workspace_bytes(const lckv_cache *c, int32_t B, int32_t max_len_hint, size_t *bytes) {
-    int rc = lckv_workspace_bytes(c, B, max_len_hint, bytes);
+    int rc = partials_bytes(c, B, max_len_hint, false, bytes);
     if (rc == LCKV_OK) *bytes *= 2;  // two sets of split partials, taken in turn by layer parity
     return rc;
 }
@@ -567,7 +601,7 @@ int lckv_step_one_launch(lckv_cache *c, const void *q_all, const void *k_new_all
         !aligned(dev_seq_lens, 4))
         return LCKV_ERR_ALIGN;
     size_t one = 0;
-    rc = lckv_workspace_bytes(c, B, max_len_hint, &one);
+    rc = partials_bytes(c, B, max_len_hint, false, &one);
     if (rc != LCKV_OK) return rc;
     if (one > 0 && (!workspace || !aligned(workspace, 256) || workspace_bytes < 2 * one)) return LCKV_ERR_WORKSPACE;
     if (c->host_only) return LCKV_ERR_HIP;
@@ -582,6 +616,7 @@ int lckv_step_one_launch(lckv_cache *c, const void *q_all, const void *k_new_all
     sp.a.Hkv = cfg.Hkv;
     sp.a.G = cfg.Hq / cfg.Hkv;
     sp.a.scale_log2e = c->scale * 1.4426950408889634f;
+    sp.a.waves = 4;
     sp.a.unit_mul = 1;
     for (int prime : {2731, 1571, 7919, 104729})  // as in the per-layer launch
         if (((int64_t)B * cfg.Hkv) % prime != 0) {
@@ -591,7 +626,7 @@ int lckv_step_one_launch(lckv_cache *c, const void *q_all, const void *k_new_all
     int max_units = 1;
     for (int vis = 0; vis < 2; ++vis) {
         const int max_n = visible_bound(c, max_len_hint, vis);
-        const SplitPlan plan = plan_splits(c, B, max_n);
+        const SplitPlan plan = plan_splits(c, B, max_n, false);  // this kernel's workgroups have four waves
         sp.max_n[vis] = max_n;
         sp.split_tokens[vis] = plan.tokens;
         sp.n_splits[vis] = plan.n_splits;
@@ -639,13 +674,7 @@ int lckv_step_static_scratch(lckv_cache *c, const void *q_all, const void *k_new
 }
 
 int lckv_workspace_bytes(const lckv_cache *c, int32_t B, int32_t max_len_hint, size_t *bytes) {
-    if (!valid(c) || !bytes) return LCKV_ERR_NULL;
-    if (B < 1 || B > c->cfg.B_max) return LCKV_ERR_BATCH;
-    if (max_len_hint < 0) return LCKV_ERR_LENGTH;
-    size_t a = workspace_need(c, B, plan_splits(c, B, visible_bound(c, max_len_hint, 0)).n_splits);
-    size_t b = workspace_need(c, B, plan_splits(c, B, visible_bound(c, max_len_hint, 1)).n_splits);
-    *bytes = a > b ? a : b;
-    return LCKV_OK;
+    return partials_bytes(c, B, max_len_hint, true, bytes);
 }
 
 // Workspace of lckv_project_qkv: none for bf16 caches (one launch, sums stay on chip); fp32 caches (parity mode):
@@ -710,6 +739,13 @@ int lckv_project_qkv(lckv_cache *c, int32_t layer, const void *x, int32_t hidden
                                   dev_seq_lens, B, c->cfg.Hq, c->cfg.Hkv, c->cfg.D, c->cfg.dtype, rope_base, acc,
                                   c->dev_err, (hipStream_t)hip_stream);
     return e == hipSuccess ? LCKV_OK : LCKV_ERR_HIP;
+}
+
+int lckv_set_workgroup_waves(lckv_cache *c, int32_t waves) {
+    if (!valid(c)) return LCKV_ERR_NULL;
+    if (waves != 0 && waves != 4 && waves != 8 && waves != 16) return LCKV_ERR_CONFIG;
+    c->forced_waves = waves;
+    return LCKV_OK;
 }
 
 int lckv_set_split_tokens(lckv_cache *c, int32_t tokens) {

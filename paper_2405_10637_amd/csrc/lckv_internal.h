@@ -156,6 +156,7 @@ struct AttnParams {
     int32_t clamp_is_policy;    // 1: n_b > max_n is the sink + window policy at work, not an error
     int32_t split_tokens;       // keys per split (multiple of 16)
     int32_t n_splits;
+    int32_t waves;              // bf16 kernel: waves per workgroup (4, 8 or 16)
     float scale_log2e;          // scale * log2(e)
     int32_t nontemporal;        // 1: read K/V with the nontemporal hint (stream larger than the caches)
     int32_t unit_mul;           // launch order -> (sequence, kv head): unit = (id * unit_mul) mod (B * Hkv), coprime
@@ -221,6 +222,7 @@ struct lckv_cache {
     int32_t max_blocks;
     int32_t capacity;
     int32_t forced_split_tokens;
+    int32_t forced_waves;         // 0: the planner chooses the workgroup width
     int32_t load_policy;          // LCKV_LOAD_*
     int32_t prefill_query_blocks; // 16-position blocks per wave in the bf16 prefill kernel (2 or 4)
     int32_t *dev_err;

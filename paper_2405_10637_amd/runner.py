@@ -17,7 +17,7 @@ DEV = "cuda"
 
 class DecodeSession:
     def __init__(self, wl: synth.Workload, room: int = 16, rule: int = lk.LCKV_PAIR_TOP_OF_CONDENSED,
-                 split_tokens: int = 0):
+                 split_tokens: int = 0, waves: int = 0):
         """`room`: how many decode steps the cache must be able to take beyond the initial lengths."""
         self.wl = wl
         self.lens0 = synth.seq_lens(wl)
@@ -38,6 +38,8 @@ class DecodeSession:
             lk.lckv_cache_set_block_table(self.h, self.table, self.table.shape[1])
         if split_tokens:
             lk.lckv_set_split_tokens(self.h, split_tokens)
+        if waves:
+            lk.lckv_set_workgroup_waves(self.h, waves)
         self.n_slots = lk.lckv_n_slots(self.h)
         self.kv_slot = [lk.lckv_kv_slot(self.h, l) for l in range(wl.L)]      # (slot, self_visible) per layer
         self.producer = [lk.lckv_slot_producer(self.h, s) for s in range(self.n_slots)]

@@ -32,7 +32,7 @@ class GpuCache:
     """A cache on the GPU for workload `wl`: storage poisoned with NaN bit patterns, optional block table."""
 
     def __init__(self, wl: synth.Workload, T_cap: int, lens: np.ndarray, rule=lk.LCKV_PAIR_TOP_OF_CONDENSED,
-                 split_tokens: int = 0, scale: float = 0.0, poison: bool = True, load_policy: int = 0,
+                 split_tokens: int = 0, scale: float = 0.0, poison: bool = True, load_policy: int = 0, waves: int = 0,
                  sink: int = 0, window: int = 0):
         self.wl = wl
         self.lens0 = np.asarray(lens, np.int32).copy()
@@ -57,6 +57,8 @@ class GpuCache:
             lk.lckv_cache_set_block_table(self.h, self.table, self.table.shape[1])
         if split_tokens:
             lk.lckv_set_split_tokens(self.h, split_tokens)
+        if waves:
+            lk.lckv_set_workgroup_waves(self.h, waves)
         lk.lckv_set_load_policy(self.h, load_policy)
         self.n_slots = lk.lckv_n_slots(self.h)
         self.lens = torch.from_numpy(self.lens0).to(DEV)

@@ -175,6 +175,30 @@ def test_argument_errors_of_the_step_and_attention_calls():
     lk.lckv_cache_free(h)
 
 
+def test_plan_replaces_few_splits_by_one_wide_workgroup():
+    # two planned splits -> one workgroup of 8 waves; three or four -> 16 waves at D = 64 only; no split partials
+    # then, hence no workspace.  Forcing the width to 4 (or forcing the split size) brings the splits back.
+    for D, T, splits_at_4, wide in [(128, 1100, 2, True), (128, 1700, 3, False), (64, 2048, 2, True),
+                                    (64, 3100, 3, True), (64, 4100, 4, True), (64, 5200, 5, False)]:
+        wl = synth.Workload("plan", "bf16", L=3, w=1, Hq=8, Hkv=2, D=D, B=2, T=T, seed=5)
+        h, _ = host_handle(wl)
+        rows = splits_at_4 * 2 * 8
+        with_splits = rows * D * 4 + (rows * 8 + 255) // 256 * 256
+        assert lk.lckv_workspace_bytes(h, 2, T) == (0 if wide else with_splits), (D, T)
+        lk.lckv_set_workgroup_waves(h, 4)
+        assert lk.lckv_workspace_bytes(h, 2, T) == with_splits, (D, T)
+        lk.lckv_set_workgroup_waves(h, 16)                       # a forced width keeps the planned splits
+        assert lk.lckv_workspace_bytes(h, 2, T) == with_splits, (D, T)
+        lk.lckv_set_workgroup_waves(h, 0)
+        assert lk.lckv_step_one_launch_workspace_bytes(h, 2, T) == 2 * with_splits   # its workgroups stay at 4 waves
+        assert code_of(lk.lckv_set_workgroup_waves, h, 12) == lk.LCKV_ERR_CONFIG
+        lk.lckv_cache_free(h)
+    wl = synth.Workload("plan32", "f32", L=3, w=1, Hq=8, Hkv=2, D=64, B=2, T=1100, seed=5)   # fp32: never wide
+    h, _ = host_handle(wl)
+    assert lk.lckv_workspace_bytes(h, 2, 1100) > 0
+    lk.lckv_cache_free(h)
+
+
 def test_static_scratch_entry_point_rejects_what_does_not_fit():
     # the variant of lckv_step for callers that cannot allocate: same checks, and a bound on the split partials
     wl = synth.Workload("static", "bf16", L=4, w=2, Hq=32, Hkv=32, D=128, B=128, T=4096, seed=3)

@@ -14,13 +14,13 @@ from gpu_harness import GpuCache, bits, check_close, to_f32_numpy
 pytestmark = pytest.mark.gpu
 
 
-def run_case(wl, lens, T_cap, rule=0, split_tokens=0, steps=2, scale=0.0):
+def run_case(wl, lens, T_cap, rule=0, split_tokens=0, steps=2, scale=0.0, waves=0):
     """Load seeded caches, run `steps` decode steps on GPU and oracle, compare outputs, caches and lengths."""
     print("case", wl.name, wl.dtype, "L", wl.L, "H", wl.Hq, wl.Hkv, "D", wl.D, "B", wl.B, "lens", list(lens)[:8],
-          "paged", wl.paged, "split", split_tokens, "rule", rule, flush=True)
+          "paged", wl.paged, "split", split_tokens, "rule", rule, "waves", waves, flush=True)
     lens = np.asarray(lens, np.int32)
     slot_o, vis_o, prod_o = orc.pairing(wl.warmup_mask, rule)
-    with GpuCache(wl, T_cap, lens, rule=rule, split_tokens=split_tokens, scale=scale) as gc:
+    with GpuCache(wl, T_cap, lens, rule=rule, split_tokens=split_tokens, scale=scale, waves=waves) as gc:
         # pairing table of the library against the oracle's
         assert gc.n_slots == len(prod_o)
         for l in range(wl.L):
@@ -94,8 +94,41 @@ def test_bf16_gqa16_d64_single_split_no_workspace():
 
 
 def test_bf16_auto_split_plan_spans_several_splits():
-    wl = synth.Workload("t-auto", "bf16", L=3, w=2, Hq=8, Hkv=2, D=128, B=2, T=1100, sigma=0.5, seed=15)
-    run_case(wl, [1100, 700], T_cap=1104, steps=1)
+    # D = 128, 4 units: the planner's own choice is three splits of 576 keys (workgroups of four waves)
+    wl = synth.Workload("t-auto", "bf16", L=3, w=2, Hq=8, Hkv=2, D=128, B=2, T=1700, sigma=0.5, seed=15)
+    with GpuCache(wl, 1704, np.array([1700, 700], np.int32)) as gc:
+        assert lk.lckv_workspace_bytes(gc.h, 2, 1700) == 3 * 2 * 8 * 128 * 4 + 512
+    run_case(wl, [1700, 700], T_cap=1704, steps=1)
+
+
+def test_bf16_auto_plan_of_two_splits_becomes_one_workgroup_of_eight_waves():
+    wl = synth.Workload("t-auto8", "bf16", L=3, w=2, Hq=8, Hkv=2, D=128, B=2, T=1100, sigma=0.5, seed=15)
+    with GpuCache(wl, 1104, np.array([1100, 700], np.int32)) as gc:
+        assert lk.lckv_workspace_bytes(gc.h, 2, 1100) == 0          # no split partials: the waves merge in LDS
+        lk.lckv_set_workgroup_waves(gc.h, 4)
+        assert lk.lckv_workspace_bytes(gc.h, 2, 1100) == 2 * 2 * 8 * 128 * 4 + 2 * 2 * 8 * 8
+    run_case(wl, [1100, 700], T_cap=1104, steps=2)
+
+
+def test_bf16_auto_plan_of_three_splits_becomes_one_workgroup_of_sixteen_waves_at_d64():
+    wl = synth.Workload("t-auto16", "bf16", L=3, w=1, Hq=16, Hkv=2, D=64, B=3, T=3100, sigma=0.5, seed=19)
+    with GpuCache(wl, 3104, np.array([3100, 0, 1500], np.int32)) as gc:
+        assert lk.lckv_workspace_bytes(gc.h, 3, 3100) == 0
+        lk.lckv_set_workgroup_waves(gc.h, 4)
+        assert lk.lckv_workspace_bytes(gc.h, 3, 3100) > 0
+    run_case(wl, [3100, 0, 1500], T_cap=3104, steps=2)
+
+
+@pytest.mark.parametrize("waves,D,paged,split", [(8, 128, False, 0), (8, 128, True, 48), (8, 64, False, 0),
+                                                 (16, 64, False, 0), (16, 64, True, 64), (16, 128, False, 0)],
+                         ids=["w8-d128", "w8-d128-paged-splits", "w8-d64", "w16-d64", "w16-d64-paged-splits",
+                              "w16-asked-at-d128-runs-as-8"])
+def test_bf16_forced_workgroup_widths(waves, D, paged, split):
+    """Workgroups of 8 and 16 waves, alone and together with splits, on ragged lengths: fewer pages than waves,
+    none at all, a partly filled last page."""
+    wl = synth.Workload("t-wide", "bf16", L=3, w=1, Hq=8, Hkv=2, D=D, B=7, T=300, sigma=1.0, seed=20 + waves + D,
+                        paged=paged)
+    run_case(wl, [300, 0, 1, 16, 17, 129, 255], T_cap=304, split_tokens=split, steps=2, waves=waves)
 
 
 def test_bf16_all_warmup_is_standard_attention():
