@@ -98,10 +98,14 @@ __global__ void pack_weight_bf16_kernel(const uint16_t *src, uint16_t *dst, int 
 
 // The end of both bf16 kernels: the four waves' sums over their quarters of the hidden dimension are added in a
 // fixed order (the result does not depend on the launch), rotated, rounded once and stored.
+// `len_of` holds the cached lengths of the sequences this lane finishes (block wave + 4 k in entry k; -1 past the
+// batch) and `freq` the table of turns per position in LDS: both were fetched when the kernel started, so that no
+// round trip to memory is left between the last matrix instruction and the stores.
 template <int TILES, int NB>
 __device__ __forceinline__ void project_reduce_and_store(const ProjParams &p, char *lds, int slot_bytes,
                                                          const floatx4 (&acc)[TILES][NB], int tg, int b0, int wave,
-                                                         int lane) {
+                                                         int lane, const int (&len_of)[(NB + 3) / 4],
+                                                         const double *freq) {
     // wave w's sums live in its own slot of the LDS (the one its x chunks went through): [tile][block][lane]
     auto red = [&](int w, int nt, int j) -> floatx4 & {
         return *(floatx4 *)(lds + w * slot_bytes + ((nt * NB + j) * 64 + lane) * 16);
@@ -112,10 +116,12 @@ __device__ __forceinline__ void project_reduce_and_store(const ProjParams &p, ch
 #pragma unroll
         for (int j = 0; j < NB; ++j) red(wave, nt, j) = acc[nt][j];
     __syncthreads();
-    for (int j = wave; j < NB; j += 4) {  // wave w finishes sequence block w
+#pragma unroll
+    for (int jk = 0; jk < (NB + 3) / 4; ++jk) {  // wave w finishes sequence blocks w, w + 4, ...
+        const int j = wave + 4 * jk;
+        if (j >= NB) break;
         const int b = b0 + 16 * j + c;
-        int t_pos = 0;
-        if (b < p.B) t_pos = max(p.seq_lens[b], 0);
+        const int t_pos = max(len_of[jk], 0);
 #pragma unroll
         for (int nt = 0; nt < TILES; ++nt) {
             floatx4 y = red(0, nt, j);
@@ -133,7 +139,7 @@ __device__ __forceinline__ void project_reduce_and_store(const ProjParams &p, ch
                 swap_halves32(lo, hi);
                 float cs = 1.f, sn = 0.f;
                 if (p.rotate && !is_v) {
-                    const double turns = (double)t_pos * p.rev_freq[i0 + e];
+                    const double turns = (double)t_pos * freq[i0 + e];
                     const float fr = (float)(turns - floor(turns));
                     sn = __builtin_amdgcn_sinf(fr);  // sine and cosine of 2 pi fr
                     cs = __builtin_amdgcn_cosf(fr);
@@ -153,7 +159,7 @@ __device__ __forceinline__ void project_reduce_and_store(const ProjParams &p, ch
                 continue;
             }
             // into the slot at position t_b (the ring entry under the sink + window policy)
-            int entry = p.seq_lens[b];
+            int entry = len_of[jk];
             if (entry >= 0) entry = entry_of_position(p.slot, entry);
             if (entry < 0 || entry >= p.slot.capacity) {
                 if (d0 == 0) atomicOr(p.dev_err, LCKV_DEV_ERR_CAPACITY);
@@ -195,6 +201,7 @@ __global__ __launch_bounds__(256) void project_staged_bf16_kernel(ProjParams p) 
     constexpr int kRed = TILES * NB * 64 * 16;
     constexpr int kSlot = kStage > kRed ? kStage : kRed;
     __shared__ __attribute__((aligned(16))) char xs[4][kSlot];
+    __shared__ __attribute__((aligned(16))) double sm_freq[64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, kb = lane >> 4;
@@ -203,6 +210,15 @@ __global__ __launch_bounds__(256) void project_staged_bf16_kernel(ProjParams p) 
     const int tg = (id / (8 * p.n_bparts)) * 8 + id % 8, bp = (id / 8) % p.n_bparts;
     if (tg >= n_groups) return;  // uniform
     const int b0 = bp * (16 * NB);
+    // what the end of the kernel needs from memory, asked for now: the rotation table (read by the waves after
+    // the barrier that precedes the final sum) and the lengths of the sequences this lane will finish
+    if (tid < 64) sm_freq[tid] = p.rev_freq[tid];
+    int len_of[(NB + 3) / 4];
+#pragma unroll
+    for (int jk = 0; jk < (NB + 3) / 4; ++jk) {
+        const int b = b0 + 16 * (wave + 4 * jk) + c;
+        len_of[jk] = (wave + 4 * jk < NB && b < p.B) ? p.seq_lens[b] : -1;
+    }
     const int ks_w = p.hidden / 128;          // steps of 32 channels per wave; a multiple of KS (checked by the host)
     const int k_begin = wave * ks_w;
     const char *wimg[TILES];
@@ -277,7 +293,7 @@ __global__ __launch_bounds__(256) void project_staged_bf16_kernel(ProjParams p) 
         use_chunk(wb);
         if (ch + 2 < n_chunks) park_x();
     }
-    project_reduce_and_store<TILES, NB>(p, &xs[0][0], kSlot, acc, tg, b0, wave, lane);
+    project_reduce_and_store<TILES, NB>(p, &xs[0][0], kSlot, acc, tg, b0, wave, lane, len_of, sm_freq);
 }
 
 // Launch 1, fp32 (parity mode, not tuned): one thread per output, products accumulated in double.
