@@ -48,7 +48,9 @@ class DecodeSession:
         self.steps_left = room
         self.import_GBps = []     # read + write rate of each lckv_cache_load_dense call made by fill()
         ws = max(lk.lckv_workspace_bytes(self.h, wl.B, self.max_len + i) for i in range(room + 1))
-        self.workspace = torch.empty(max(2 * ws, 256), dtype=torch.uint8, device=DEV)   # 2x: the one-launch step's
+        if wl.dtype == "bf16":   # the one-launch step sizes its own (two sets of partials, workgroups of four waves)
+            ws = max([ws] + [lk.lckv_step_one_launch_workspace_bytes(self.h, wl.B, self.max_len + i) for i in range(room + 1)])
+        self.workspace = torch.empty(max(ws, 256), dtype=torch.uint8, device=DEV)
 
     def close(self):
         if self.h:
