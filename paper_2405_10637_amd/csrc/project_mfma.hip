@@ -432,10 +432,11 @@ hipError_t launch_project(const void *x, int hidden, const void *w_q, const void
         if (D / 2 > 64) return hipErrorInvalidValue;
         for (int i = 0; i < D / 2; ++i)
             p.rev_freq[i] = p.rotate ? pow((double)rope_base, -2.0 * i / D) / 6.283185307179586476925286766559 : 0.0;
-        // up to 64 sequences per workgroup; batches up to 64 take one tile per workgroup (more workgroups, each
-        // reading all of x), small ones longer chunks (more weight bytes in flight per wave)
-        const int per_part = B > 32 ? 64 : B > 16 ? 32 : 16;
-        const int tiles = B > 64 ? 2 : 1;  // measured: B = 64: 0.54 ms per step with one tile, 0.62 with two; B = 128: 0.89 / 0.69
+        // Sequences and feature tiles per workgroup, measured on the Llama-7B shape (ms per step): B = 64: 32 x 2
+        // tiles 0.49, 64 x 1 tile 0.54, 64 x 2 tiles 0.62; B = 128: 64 x 2 tiles 0.66, 32 x 4 tiles 0.70, 64 x 1 tile
+        // 0.89.  (n_total is a multiple of 64: whole heads of at least 64 channels.)
+        const int per_part = B > 64 ? 64 : B > 16 ? 32 : 16;
+        const int tiles = B > 32 ? 2 : 1;
         p.n_bparts = (B + per_part - 1) / per_part;
         const int n_groups = p.n_total / (16 * tiles);
         dim3 grid((unsigned)((n_groups + 7) / 8 * 8 * p.n_bparts));
@@ -448,11 +449,9 @@ hipError_t launch_project(const void *x, int hidden, const void *w_q, const void
 #define LCKV_PROJECT_LAUNCH(T, NB, KS) \
     hipLaunchKernelGGL((project_staged_bf16_kernel<T, NB, KS>), grid, dim3(256), 0, s, p)
         if (per_part == 64) {
-            if (tiles == 2) {
-                if (ks == 4) LCKV_PROJECT_LAUNCH(2, 4, 4); else LCKV_PROJECT_LAUNCH(2, 4, 2);
-            } else {
-                if (ks == 4) LCKV_PROJECT_LAUNCH(1, 4, 4); else LCKV_PROJECT_LAUNCH(1, 4, 2);
-            }
+            if (ks == 4) LCKV_PROJECT_LAUNCH(2, 4, 4); else LCKV_PROJECT_LAUNCH(2, 4, 2);
+        } else if (per_part == 32 && tiles == 2) {
+            if (ks >= 4) LCKV_PROJECT_LAUNCH(2, 2, 4); else LCKV_PROJECT_LAUNCH(2, 2, 2);
         } else if (per_part == 32) {
             if (ks == 8) LCKV_PROJECT_LAUNCH(1, 2, 8); else if (ks == 4) LCKV_PROJECT_LAUNCH(1, 2, 4); else LCKV_PROJECT_LAUNCH(1, 2, 2);
         } else {

@@ -91,7 +91,7 @@ def test_project_bf16_mha_d128_paged_two_passes():
     run_project(wl, 512, lens, 48)
 
 
-@pytest.mark.parametrize("B", [16, 17, 33, 64])
+@pytest.mark.parametrize("B", [16, 17, 33, 48, 64, 65])
 def test_project_bf16_batch_blocks(B):
     wl = synth.Workload("pr-b%d" % B, "bf16", L=2, w=1, Hq=3, Hkv=1, D=64, B=B, T=20, sigma=1.0, seed=63 + B,
                         warm=(0,))
