@@ -14,13 +14,14 @@ from gpu_harness import GpuCache, bits, check_close, to_f32_numpy
 pytestmark = pytest.mark.gpu
 
 
-def run_case(wl, lens, T_cap, rule=0, split_tokens=0, steps=2, scale=0.0, waves=0):
+def run_case(wl, lens, T_cap, rule=0, split_tokens=0, steps=2, scale=0.0, waves=0, load_policy=0):
     """Load seeded caches, run `steps` decode steps on GPU and oracle, compare outputs, caches and lengths."""
     print("case", wl.name, wl.dtype, "L", wl.L, "H", wl.Hq, wl.Hkv, "D", wl.D, "B", wl.B, "lens", list(lens)[:8],
           "paged", wl.paged, "split", split_tokens, "rule", rule, "waves", waves, flush=True)
     lens = np.asarray(lens, np.int32)
     slot_o, vis_o, prod_o = orc.pairing(wl.warmup_mask, rule)
-    with GpuCache(wl, T_cap, lens, rule=rule, split_tokens=split_tokens, scale=scale, waves=waves) as gc:
+    with GpuCache(wl, T_cap, lens, rule=rule, split_tokens=split_tokens, scale=scale, waves=waves,
+                  load_policy=load_policy) as gc:
         # pairing table of the library against the oracle's
         assert gc.n_slots == len(prod_o)
         for l in range(wl.L):
@@ -125,10 +126,12 @@ def test_bf16_auto_plan_of_three_splits_becomes_one_workgroup_of_sixteen_waves_a
                               "w16-asked-at-d128-runs-as-8"])
 def test_bf16_forced_workgroup_widths(waves, D, paged, split):
     """Workgroups of 8 and 16 waves, alone and together with splits, on ragged lengths: fewer pages than waves,
-    none at all, a partly filled last page."""
+    none at all, a partly filled last page; with plain and with nontemporal loads (separate kernel variants)."""
     wl = synth.Workload("t-wide", "bf16", L=3, w=1, Hq=8, Hkv=2, D=D, B=7, T=300, sigma=1.0, seed=20 + waves + D,
                         paged=paged)
-    run_case(wl, [300, 0, 1, 16, 17, 129, 255], T_cap=304, split_tokens=split, steps=2, waves=waves)
+    for policy in (lk.LCKV_LOAD_TEMPORAL, lk.LCKV_LOAD_NONTEMPORAL):
+        run_case(wl, [300, 0, 1, 16, 17, 129, 255], T_cap=304, split_tokens=split, steps=2, waves=waves,
+                 load_policy=policy)
 
 
 def test_bf16_all_warmup_is_standard_attention():
