@@ -394,7 +394,7 @@ def main():
     K, W = args.steps, args.warmup
 
     # capacity: the initial length plus every step this run takes (graph mode runs K replays and K eager steps)
-    room = (2 * K if args.graph else K) + W + 2
+    room = 2 * K + W + 2   # timed steps + a second pass (graph: with launch events; otherwise: without them)
     if args.capacity:
         if args.capacity < wl.T + room:
             sys.exit("--capacity must be at least %d for this run" % (wl.T + room))
@@ -465,6 +465,17 @@ def main():
     n_launch, kern_ms = lk.lckv_profile_read(sess.h)
     lk.lckv_profile_enable(sess.h, False)
     assert lk.lckv_last_device_error(sess.h) == 0
+    # The timed steps carry two HIP events per launch (the kernel's duration for the roofline comes from them).  An
+    # event costs a few microseconds on the stream: nothing next to a 1 ms launch, a quarter of a step where a
+    # launch lasts 20 us.  A second pass of K steps without them says what the step costs a caller who records none.
+    ms_plain = None
+    if not args.graph and sess.steps_left >= K:
+        torch.cuda.synchronize()
+        tp0 = time.perf_counter()
+        for _ in range(K):
+            one_step()
+        torch.cuda.synchronize()
+        ms_plain = (time.perf_counter() - tp0) * 1e3 / K
 
     # what a pure read with the same load pattern reaches on this device (context for the roofline fraction)
     probe_bytes = min(sess.cache_bytes, 16 << 30) // (2 << 20) * (2 << 20)
@@ -503,6 +514,7 @@ def main():
             wl.T if wl.T_min is None else "U[%d,%d]" % (wl.T_min, wl.T), " paged16" if wl.paged else ""),
             "slots": sess.n_slots, "cache_GiB": round(sess.cache_bytes / 2 ** 30, 2)},
         "step_effective_GBps": step_gbps, "step_pct_of_hbm_peak": 100.0 * step_gbps / HBM_PEAK_GBPS,
+        "ms_per_step_without_launch_events": ms_plain,
         "read_probe_GBps": probe_gbps,
         "cache_fill_import_GBps": [round(x, 1) for x in sess.import_GBps],   # lckv_cache_load_dense, read + write
         "roofline": {"bound": "hbm", "kernel": "step_bf16_kernel" if args.one_launch else
