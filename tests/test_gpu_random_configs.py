@@ -48,7 +48,8 @@ def test_decode_step_random_config(seed):
     lens = random_lens(rng, wl.B, top)
     split = int(rng.choice([0, 16, 32, 64]))
     rule = int(rng.integers(0, 2))
-    run_case(wl.with_(T=top), lens, top + 8, rule=rule, split_tokens=split, steps=2)
+    waves = int(rng.choice([0, 0, 4, 8, 16]))                      # workgroup width of the bf16 kernel (fp32 ignores it)
+    run_case(wl.with_(T=top), lens, top + 8, rule=rule, split_tokens=split, steps=2, waves=waves)
 
 
 @pytest.mark.parametrize("seed", range(12 * MORE))
