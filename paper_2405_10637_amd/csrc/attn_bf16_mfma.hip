@@ -308,8 +308,9 @@ static hipError_t launch_variant(const AttnParams &p, hipStream_t s) {
 }
 
 hipError_t launch_attn_bf16(const AttnParams &p, int D, hipStream_t s) {
-    // One page per wave and tile: measured fastest on MI355X for the Llama-7B shape (three waves per SIMD fit in
-    // the register file; two- and four-page tiles were 1-2 % slower).  Workgroups of 8 or 16 waves stand in for
+    // One page per wave and tile: measured fastest on MI355X for the Llama-7B shape (two- and four-page tiles were
+    // 1-2 % slower).  At D = 128 the kernel takes 185 registers, i.e. two waves per SIMD; cut to the 168 that three
+    // waves would allow it spills inside the loop and the step takes 47.9 instead of 39.9 ms.  Workgroups of 8 or 16 waves stand in for
     // two or up to four splits (the host's plan): the merge of the waves through LDS is then the whole merge.
     if (p.waves != 4 && p.waves != 8 && !(p.waves == 16 && D == 64)) return hipErrorInvalidValue;
     if (D == 128) return p.waves == 8 ? launch_variant<128, 1, 8>(p, s) : launch_variant<128, 1, 4>(p, s);
